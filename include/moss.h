@@ -1,0 +1,184 @@
+/*
+ * moss.h -- C ABI of the MI355X (gfx950) implementation of the MOSS FP8 hot path
+ * (arXiv 2511.05811): two-level microscaled FP8 quantization of activations and
+ * gradients, per-tensor FP8 weights with automatic scaling fused into the AdamW
+ * step, and the block-scaled FP8 GEMMs of a linear layer.
+ *
+ * Conventions for every entry point
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *    allocates nothing and keeps no hidden state besides cached device properties.
+ *    Pointers to `moss_adamw_args` are HOST pointers (read during the call).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *    work is enqueued asynchronously on it; nothing synchronizes with the host.
+ *  - Scales travel as device scalars, so chaining quantizer -> GEMM needs no host
+ *    round trip.
+ *  - Argument errors are detected on the host before anything is launched and are
+ *    returned as a negative-free status code (never an abort, never an exception).
+ *  - Inputs must be finite.  Tensor base pointers and leading dimensions must be
+ *    16-byte aligned unless stated otherwise.
+ *  - `workspace` is device scratch of at least the size the matching
+ *    *_workspace_bytes() call reports; contents need not be initialised and are
+ *    clobbered.  Two calls that share a workspace must be ordered on one stream.
+ */
+#ifndef MOSS_H
+#define MOSS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOSS_OK = 0,
+    MOSS_ERR_NULL = 1,        /* a required pointer is NULL */
+    MOSS_ERR_SHAPE = 2,       /* a size is non-positive or not a multiple of the group size */
+    MOSS_ERR_ALIGN = 3,       /* a pointer or leading dimension is not 16-byte aligned */
+    MOSS_ERR_WORKSPACE = 4,   /* workspace missing or too small */
+    MOSS_ERR_UNSUPPORTED = 5, /* flag / dtype combination not implemented */
+    MOSS_ERR_HIP = 6          /* the HIP runtime reported an error (launch, query) */
+} moss_status;
+
+const char *moss_status_string(int status);
+
+/* Number of compute units of the current device (0 if no device is usable). */
+int moss_device_cu_count(void);
+
+/* ---- element types of operands that come in more than one type -------------- */
+#define MOSS_DT_BF16 0
+#define MOSS_DT_F32 1
+
+/* ---------------------------------------------------------------------------
+ * Two-level microscaling quantizer  (paper Sec. 3.1, Eq. 1 and Eq. 2, and the
+ * quantize / dequantize maps Q = round(X / (s ss_i)),  DQ = Q s ss_i).
+ *
+ *   x        BF16 [rows x cols], row stride `ld` elements.
+ *   s        one FP32 global scale per tensor:  s = amax(X) / 448  (s = 1 for an
+ *            all-zero tensor); written to *s_global (device).
+ *   ss_i     one power of two per group of 32 elements, ss_i = 2^(e_i),
+ *            e_i = round(log2(amax_i / amax)) in [-127, 0]  (MOSS_EXP_NEAREST, the
+ *            paper's "closest power of two"), or the ceiling (MOSS_EXP_CEIL, which
+ *            never saturates a code).  Stored as the E8M0 byte e_i + 127; an
+ *            all-zero group stores byte 0.
+ *   codes    E4M3 (max 448) of  y = fl32(x * fl32(1/s)) * 2^(-e_i), rounded to
+ *            nearest even, saturated to +-448, sign kept.
+ *
+ * MOSS_Q_ROW: groups run along the columns (the inner dimension of Y = X W^T and
+ *             of dX = dY W): q_row [rows x cols], e_row [rows x cols/32].
+ * MOSS_Q_COL: groups run along the rows (the inner dimension of dW = dY^T X), and
+ *             the outputs are stored transposed so that the groups are contiguous:
+ *             q_col [cols x rows], e_col [cols x rows/32].
+ * Both flags may be set in one call; both outputs then share the one global scale.
+ *
+ * Requirements: cols % 32 == 0; rows % 32 == 0 if MOSS_Q_COL; ld >= cols, ld % 8 == 0.
+ * Outputs are dense (no padding).  Returns MOSS_OK or an argument / HIP error.
+ * ------------------------------------------------------------------------- */
+#define MOSS_Q_ROW 1u
+#define MOSS_Q_COL 2u
+#define MOSS_EXP_NEAREST 0u
+#define MOSS_EXP_CEIL 4u
+
+size_t moss_quant_workspace_bytes(int64_t rows, int64_t cols, unsigned flags);
+
+int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                          uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
+                          float *s_global, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Per-tensor FP8 weights with automatic scaling  (paper Sec. 3.2, Eq. 6 and the
+ * interval re-scaling of its last paragraph; AdamW as in Sec. 2.2 Eq. 3; App. C).
+ *
+ * The state is a small plain struct in DEVICE memory that the caller owns and may
+ * copy out / back in to checkpoint a run.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    float s_base;            /* s_0: amax(W)/448 at the last max-reduction */
+    float s_cur;             /* s_t: scale of the latest cast (Eq. 6) */
+    double cum_lr;           /* sum of margin*lr since the last max-reduction ("eta t") */
+    int64_t step;            /* optimizer steps taken */
+    int64_t last_rebase;     /* step of the last max-reduction */
+    float amax_seen;         /* amax of the weights at the latest cast (free by-product) */
+    uint32_t overflow_count; /* elements whose scaled value exceeded 448 and was clipped, cumulative */
+} moss_wscale_state;
+
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    float one_minus_beta1, one_minus_beta2; /* 1-beta, rounded to FP32 by the caller */
+    float bias_corr1, bias_corr2;           /* 1-beta^t, rounded to FP32 by the caller */
+    float margin;                           /* multiplies lr in the prediction; the paper's rule is 1 */
+    int32_t interval;                       /* max-reduction every `interval` steps; <= 0: never */
+    int64_t step;                           /* number t of the step this call performs (1-based);
+                                               must equal state.step + 1 */
+} moss_adamw_args;
+
+size_t moss_weight_workspace_bytes(int64_t rows, int64_t cols);
+
+/* Initialisation: s_0 = amax(W_0)/448 by one max-reduction, state reset, first cast.
+ *   w      [rows x cols] dense, FP32 (MOSS_DT_F32) or BF16 (MOSS_DT_BF16); not modified.
+ *   wq     E4M3 codes [rows x cols]:  round(fl32(w * fl32(1/s)))  (all zero if s == 0).
+ *   wq_t   optional [cols x rows] byte transpose of wq (the K-contiguous operand of
+ *          dX = dY W); may be NULL.
+ * Requirements: rows * cols % 4 == 0.                                             */
+int moss_weight_autoscale_init(const void *w, int w_dtype, int64_t rows, int64_t cols,
+                               moss_wscale_state *state, uint8_t *wq, uint8_t *wq_t,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* One optimizer step with scale prediction and the FP8 cast fused in: a single
+ * streaming pass reads W, m, v, g, applies AdamW in FP32
+ *     m = b1 m + (1-b1) g;  v = b2 v + ((1-b2) g) g;
+ *     W = W - lr ( (m/bc1) / (sqrt(v/bc2) + eps) + wd W )
+ * (each operation rounded once, nothing contracted), writes W, m, v and the E4M3
+ * codes of the NEW weights under the predicted scale
+ *     cum_lr += margin*lr;   s_t = (float)(s_base + cum_lr/448)
+ * without any max-reduction pass.  amax(W_new) and the number of clipped elements
+ * are produced on the way.  If args->interval > 0 and args->step % interval == 0 the
+ * scale is re-based instead: s_base = s_t = amax(W_new)/448, cum_lr = 0, and the
+ * cast is redone with it (one extra pass over W on that step only).
+ *   w, m, v  FP32 [rows x cols], updated in place.
+ *   g        gradient, FP32 or BF16 (g_dtype).
+ * Requirements: rows * cols % 4 == 0.                                             */
+int moss_weight_autoscale_cast(float *w, float *m, float *v, const void *g, int g_dtype,
+                               int64_t rows, int64_t cols, const moss_adamw_args *args,
+                               moss_wscale_state *state, uint8_t *wq, uint8_t *wq_t,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Block-scaled FP8 GEMM with epilogue dequantization (paper Sec. 3.1, Fig. 3b:
+ * Q_y = Q_w x (Q_x * ss_x), then one multiply by s_x s_W outside the main loop).
+ *
+ *   out[m,n] (+)= a_s*b_s * sum_k  dec(a_q[m,k]) 2^(a_e[m,k/32]-127)
+ *                                 * dec(b_q[n,k]) 2^(b_e[n,k/32]-127)
+ *
+ *   a_q [M x K], b_q [N x K]   E4M3 codes, both K-contiguous, dense.
+ *   a_e [M x K/32], b_e [N x K/32]  E8M0 bytes, or NULL for the artificial unit
+ *                               scale the paper gives per-tensor weights.
+ *   a_s, b_s                    device FP32 scalars (global / per-tensor scales).
+ *   out  [M x N], row stride ld_out elements, BF16 or FP32 (out_dtype);
+ *        accumulate != 0 adds into an FP32 `out` (dW accumulation), else overwrites.
+ * The three GEMMs of a linear layer are three calls:
+ *   Y  = X W^T   : a = (Xq_row, ex_row, s_x),   b = (Wq,   NULL, s_W)   M=T, N=out, K=in
+ *   dX = dY W    : a = (dYq_row, edy_row, s_dy), b = (Wq^T, NULL, s_W)   M=T, N=in,  K=out
+ *   dW = dY^T X  : a = (dYq_col, edy_col, s_dy), b = (Xq_col, ex_col, s_x) M=out, N=in, K=T
+ * FP32 accumulation on the block-scaled FP8 matrix cores; the level-2 exponents are
+ * applied by the matrix instruction itself.
+ * Requirements: K % 32 == 0; ld_out >= N; accumulate only with MOSS_DT_F32.
+ * ------------------------------------------------------------------------- */
+size_t moss_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+int moss_gemm_fp8_mx(int64_t M, int64_t N, int64_t K,
+                     const uint8_t *a_q, const uint8_t *a_e, const float *a_s,
+                     const uint8_t *b_q, const uint8_t *b_e, const float *b_s,
+                     void *out, int out_dtype, int64_t ld_out, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Comparison baseline only (not part of the MOSS path): the same tiling on the BF16
+ * matrix cores, out[m,n] = sum_k a[m,k] b[n,k], BF16 in, FP32 accumulate, BF16 out.
+ * a [M x K], b [N x K] dense; K % 32 == 0.                                        */
+int moss_gemm_bf16_baseline(int64_t M, int64_t N, int64_t K, const void *a_bf16, const void *b_bf16,
+                            void *out_bf16, int64_t ld_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOSS_H */

@@ -1,0 +1,211 @@
+"""ctypes binding of include/moss.h.  Argument marshalling only: every step of the
+path runs in the HIP kernels.  torch is used for device memory and streams."""
+import ctypes as C
+import os
+import re
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libmoss_hip.so")
+_HEADER = os.path.join(os.path.dirname(_PKG), "include", "moss.h")
+_lib = None
+
+MOSS_DT_BF16, MOSS_DT_F32 = 0, 1
+MOSS_Q_ROW, MOSS_Q_COL = 1, 2
+MOSS_EXP_NEAREST, MOSS_EXP_CEIL = 0, 4
+
+
+class MossError(RuntimeError):
+    pass
+
+
+class WScaleState(C.Structure):
+    _fields_ = [("s_base", C.c_float), ("s_cur", C.c_float), ("cum_lr", C.c_double),
+                ("step", C.c_int64), ("last_rebase", C.c_int64),
+                ("amax_seen", C.c_float), ("overflow_count", C.c_uint32)]
+
+
+class AdamWArgs(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float),
+                ("one_minus_beta1", C.c_float), ("one_minus_beta2", C.c_float),
+                ("bias_corr1", C.c_float), ("bias_corr2", C.c_float),
+                ("margin", C.c_float), ("interval", C.c_int32), ("step", C.c_int64)]
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def exported_symbols():
+    """Names of the functions include/moss.h declares."""
+    text = open(_HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moss_[a-z0-9_]+)\s*\(", text)))
+
+
+def load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise MossError(f"{_LIB_PATH} is missing: build it with `python -m paper_2511_05811_amd.build` "
+                        "(there is no fallback path)")
+    L = C.CDLL(_LIB_PATH)
+    vp, i64, u32, sz, ci = C.c_void_p, C.c_int64, C.c_uint, C.c_size_t, C.c_int
+    L.moss_status_string.restype = C.c_char_p
+    L.moss_status_string.argtypes = [ci]
+    L.moss_device_cu_count.restype = ci
+    L.moss_quant_workspace_bytes.restype = sz
+    L.moss_quant_workspace_bytes.argtypes = [i64, i64, u32]
+    L.moss_quant_act_2level.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moss_weight_workspace_bytes.restype = sz
+    L.moss_weight_workspace_bytes.argtypes = [i64, i64]
+    L.moss_weight_autoscale_init.argtypes = [vp, ci, i64, i64, vp, vp, vp, vp, sz, vp]
+    L.moss_weight_autoscale_cast.argtypes = [vp, vp, vp, vp, ci, i64, i64, C.POINTER(AdamWArgs), vp, vp, vp, vp, sz, vp]
+    L.moss_gemm_workspace_bytes.restype = sz
+    L.moss_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+    L.moss_gemm_fp8_mx.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, ci, i64, ci, vp, sz, vp]
+    L.moss_gemm_bf16_baseline.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp]
+    _lib = L
+    return L
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise MossError(f"{what}: {load().moss_status_string(rc).decode()} (status {rc})")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def device_cu_count():
+    return load().moss_device_cu_count()
+
+
+def _workspace(nbytes, device):
+    import torch
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def quant_act_2level(x, flags=MOSS_Q_ROW, out=None, workspace=None):
+    """x: torch.bfloat16 [rows, cols] on the GPU (row stride may exceed cols).
+    Returns dict(q_row, e_row, q_col, e_col, s) of device tensors (absent outputs are None)."""
+    import torch
+    L = load()
+    rows, cols = x.shape
+    assert x.dtype == torch.bfloat16 and x.is_cuda and x.stride(1) == 1
+    ld = x.stride(0)
+    dev = x.device
+    out = out or {}
+    u8 = torch.uint8
+    want_row, want_col = bool(flags & MOSS_Q_ROW), bool(flags & MOSS_Q_COL)
+    q_row = out.get("q_row") if want_row else None
+    e_row = out.get("e_row") if want_row else None
+    q_col = out.get("q_col") if want_col else None
+    e_col = out.get("e_col") if want_col else None
+    if want_row and q_row is None:
+        q_row = torch.empty((rows, cols), dtype=u8, device=dev)
+        e_row = torch.empty((rows, cols // 32), dtype=u8, device=dev)
+    if want_col and q_col is None:
+        q_col = torch.empty((cols, rows), dtype=u8, device=dev)
+        e_col = torch.empty((cols, rows // 32), dtype=u8, device=dev)
+    s = out.get("s")
+    if s is None:
+        s = torch.empty(1, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(L.moss_quant_workspace_bytes(rows, cols, flags), dev)
+    rc = L.moss_quant_act_2level(_ptr(x), rows, cols, ld, flags, _ptr(q_row), _ptr(e_row), _ptr(q_col), _ptr(e_col),
+                                 _ptr(s), _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "moss_quant_act_2level")
+    return dict(q_row=q_row, e_row=e_row, q_col=q_col, e_col=e_col, s=s)
+
+
+def new_wscale_state(device):
+    import torch
+    return torch.zeros(C.sizeof(WScaleState), dtype=torch.uint8, device=device)
+
+
+def read_wscale_state(state):
+    """Copy the device-resident state struct to the host (synchronizes)."""
+    return WScaleState.from_buffer_copy(bytes(state.cpu().numpy().tobytes()))
+
+
+def _dt(t):
+    import torch
+    if t.dtype == torch.float32:
+        return MOSS_DT_F32
+    if t.dtype == torch.bfloat16:
+        return MOSS_DT_BF16
+    raise MossError(f"unsupported dtype {t.dtype}")
+
+
+def weight_autoscale_init(w, state, wq=None, wq_t=None, want_transpose=False, workspace=None):
+    import torch
+    L = load()
+    rows, cols = w.shape
+    assert w.is_cuda and w.is_contiguous()
+    if wq is None:
+        wq = torch.empty((rows, cols), dtype=torch.uint8, device=w.device)
+    if want_transpose and wq_t is None:
+        wq_t = torch.empty((cols, rows), dtype=torch.uint8, device=w.device)
+    if workspace is None:
+        workspace = _workspace(L.moss_weight_workspace_bytes(rows, cols), w.device)
+    rc = L.moss_weight_autoscale_init(_ptr(w), _dt(w), rows, cols, _ptr(state), _ptr(wq), _ptr(wq_t),
+                                      _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "moss_weight_autoscale_init")
+    return wq, wq_t
+
+
+def weight_autoscale_cast(w, m, v, g, args, state, wq=None, wq_t=None, want_transpose=False, workspace=None):
+    """One fused AdamW + scale prediction + FP8 cast step; w, m, v float32 in place."""
+    import torch
+    L = load()
+    rows, cols = w.shape
+    for t in (w, m, v):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
+    assert g.is_cuda and g.is_contiguous()
+    if wq is None:
+        wq = torch.empty((rows, cols), dtype=torch.uint8, device=w.device)
+    if want_transpose and wq_t is None:
+        wq_t = torch.empty((cols, rows), dtype=torch.uint8, device=w.device)
+    if workspace is None:
+        workspace = _workspace(L.moss_weight_workspace_bytes(rows, cols), w.device)
+    rc = L.moss_weight_autoscale_cast(_ptr(w), _ptr(m), _ptr(v), _ptr(g), _dt(g), rows, cols, C.byref(args),
+                                      _ptr(state), _ptr(wq), _ptr(wq_t), _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "moss_weight_autoscale_cast")
+    return wq, wq_t
+
+
+def gemm_fp8_mx(a_q, a_e, a_s, b_q, b_e, b_s, out=None, out_dtype=None, accumulate=False):
+    """out[m,n] (+)= a_s*b_s*sum_k a[m,k] 2^(ae-127) b[n,k] 2^(be-127); a_q [M,K], b_q [N,K] uint8 device tensors,
+    a_e/b_e uint8 [.,K/32] or None, a_s/b_s float32 device scalars."""
+    import torch
+    L = load()
+    M, K = a_q.shape
+    N = b_q.shape[0]
+    assert b_q.shape[1] == K and a_q.is_contiguous() and b_q.is_contiguous()
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype or torch.bfloat16, device=a_q.device)
+    rc = L.moss_gemm_fp8_mx(M, N, K, _ptr(a_q), _ptr(a_e), _ptr(a_s), _ptr(b_q), _ptr(b_e), _ptr(b_s),
+                            _ptr(out), _dt(out), out.stride(0), int(bool(accumulate)), None, 0, _stream())
+    _check(rc, "moss_gemm_fp8_mx")
+    return out
+
+
+def gemm_bf16_baseline(a, b, out=None):
+    import torch
+    L = load()
+    M, K = a.shape
+    N = b.shape[0]
+    assert a.dtype == torch.bfloat16 and b.dtype == torch.bfloat16 and a.is_contiguous() and b.is_contiguous()
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
+    rc = L.moss_gemm_bf16_baseline(M, N, K, _ptr(a), _ptr(b), _ptr(out), out.stride(0), _stream())
+    _check(rc, "moss_gemm_bf16_baseline")
+    return out

@@ -1,0 +1,270 @@
+// Block-scaled FP8 GEMM for gfx950 (paper Sec. 3.1, Fig. 3b): the main loop is
+// nothing but block-scaled matrix-core instructions (the E8M0 level-2 exponents ride
+// along as instruction operands), and the two FP32 scales are applied once in the
+// epilogue.
+//
+//   out[m,n] = a_s b_s sum_k dec(a[m,k]) 2^(ae[m,k/32]-127) dec(b[n,k]) 2^(be[n,k/32]-127)
+//
+// Both operands are K-contiguous ([M x K] and [N x K]).  One V_MFMA_SCALE_F32_16X16X128
+// consumes, per lane, 32 consecutive K bytes of one row (= exactly one level-2 group)
+// of each operand plus one scale byte per operand.  The b operand is fed as the
+// instruction's first source so that a lane ends up with four consecutive n of one
+// output row and can store them with one vector store.
+//
+// The same tiling on the BF16 matrix cores (V_MFMA_F32_16X16X32_BF16) is kept as the
+// comparison baseline.
+#include "moss_internal.h"
+
+namespace moss {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kRowBytes = 128;   // bytes of K per tile row and per main-loop step
+constexpr int kChunks = 8;       // 16-byte chunks per tile row
+
+// LDS tile: row r holds 128 bytes in 8 chunks; chunk c is stored at slot c ^ ((r>>1)&7)
+// so that the 16 rows a quarter-wave reads with one 16-byte access fall into 16
+// different bank groups.
+__device__ __forceinline__ int lds_off(int row, int chunk)
+{
+    return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4);
+}
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+enum GemmMode { kModeFp8Mx = 0, kModeBf16 = 1 };
+
+template <int BM, int BN, int WM, int WN, int MODE>
+__global__ __launch_bounds__(WM *WN * 64) void k_gemm(int64_t M, int64_t N, int64_t Kb /* bytes of K per row */,
+                                                      const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_e,
+                                                      const float *__restrict__ a_s,
+                                                      const uint8_t *__restrict__ b_q, const uint8_t *__restrict__ b_e,
+                                                      const float *__restrict__ b_s,
+                                                      void *__restrict__ out, int out_f32, int64_t ld_out, int accumulate,
+                                                      int tiles_m, int tiles_n)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
+    constexpr int FM = TM / 16, FN = TN / 16;   // 16x16 fragments per wave tile
+    constexpr int LA = BM * kChunks / NT, LB = BN * kChunks / NT;   // 16-byte loads per thread per step
+    static_assert(BM * kChunks % NT == 0 && BN * kChunks % NT == 0, "tile/threads mismatch");
+
+    __shared__ __attribute__((aligned(16))) uint8_t lds_a[BM * kRowBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_b[BN * kRowBytes];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l16 = lane & 15, lq = lane >> 4;
+
+    // tile order: consecutive workgroups walk down a column of tiles (sharing the b
+    // tile) inside bands of 8 tile-rows
+    const int tile = blockIdx.x;
+    const int tm = tile % tiles_m, tn = tile / tiles_m;
+    (void)tiles_n;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int64_t KT = (Kb + kRowBytes - 1) / kRowBytes;
+    const int64_t G = Kb / kGroup;   // level-2 groups per row (FP8 mode)
+
+    uint4 ra[LA], rb[LB];
+    auto load_global = [&](int64_t kt) {
+#pragma unroll
+        for (int i = 0; i < LA; i++) {
+            int ci = tid + i * NT, row = ci >> 3, c = ci & 7;
+            int64_t gr = m0 + row;
+            gr = gr < M ? gr : M - 1;
+            int64_t kb = kt * kRowBytes + c * 16;
+            ra[i] = kb < Kb ? *reinterpret_cast<const uint4 *>(a_q + gr * Kb + kb) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < LB; i++) {
+            int ci = tid + i * NT, row = ci >> 3, c = ci & 7;
+            int64_t gr = n0 + row;
+            gr = gr < N ? gr : N - 1;
+            int64_t kb = kt * kRowBytes + c * 16;
+            rb[i] = kb < Kb ? *reinterpret_cast<const uint4 *>(b_q + gr * Kb + kb) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < LA; i++) {
+            int ci = tid + i * NT;
+            *reinterpret_cast<uint4 *>(lds_a + lds_off(ci >> 3, ci & 7)) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < LB; i++) {
+            int ci = tid + i * NT;
+            *reinterpret_cast<uint4 *>(lds_b + lds_off(ci >> 3, ci & 7)) = rb[i];
+        }
+    };
+
+    v4f acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; i++)
+#pragma unroll
+        for (int j = 0; j < FN; j++) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    load_global(0);
+    for (int64_t kt = 0; kt < KT; kt++) {
+        store_lds();
+        __syncthreads();
+        if (kt + 1 < KT) load_global(kt + 1);
+
+        if (MODE == kModeFp8Mx) {
+            // one scale byte per lane and fragment: row (l16), group (4 kt + lq)
+            int sa[FM], sb[FN];
+            const int64_t grp = kt * 4 + lq;
+#pragma unroll
+            for (int i = 0; i < FM; i++) {
+                int64_t r = m0 + wm * TM + i * 16 + l16;
+                r = r < M ? r : M - 1;
+                sa[i] = (a_e && grp < G) ? (int)a_e[r * G + grp] : 127;
+            }
+#pragma unroll
+            for (int j = 0; j < FN; j++) {
+                int64_t r = n0 + wn * TN + j * 16 + l16;
+                r = r < N ? r : N - 1;
+                sb[j] = (b_e && grp < G) ? (int)b_e[r * G + grp] : 127;
+            }
+            v8i fa[FM], fb[FN];
+#pragma unroll
+            for (int i = 0; i < FM; i++) {
+                int row = wm * TM + i * 16 + l16;
+                uint4 lo = *reinterpret_cast<const uint4 *>(lds_a + lds_off(row, 2 * lq));
+                uint4 hi = *reinterpret_cast<const uint4 *>(lds_a + lds_off(row, 2 * lq + 1));
+                fa[i] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            }
+#pragma unroll
+            for (int j = 0; j < FN; j++) {
+                int row = wn * TN + j * 16 + l16;
+                uint4 lo = *reinterpret_cast<const uint4 *>(lds_b + lds_off(row, 2 * lq));
+                uint4 hi = *reinterpret_cast<const uint4 *>(lds_b + lds_off(row, 2 * lq + 1));
+                fb[j] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            }
+#pragma unroll
+            for (int i = 0; i < FM; i++)
+#pragma unroll
+                for (int j = 0; j < FN; j++)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i], acc[i][j], 0, 0, 0, sb[j], 0,
+                                                                                 sa[i]);
+        } else {
+            // BF16: a 128-byte row is 64 elements = two K sub-steps of 32; in each a lane
+            // holds 8 consecutive elements (one 16-byte chunk)
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++) {
+                v8bf fa[FM], fb[FN];
+#pragma unroll
+                for (int i = 0; i < FM; i++) {
+                    int row = wm * TM + i * 16 + l16;
+                    fa[i] = *reinterpret_cast<const v8bf *>(lds_a + lds_off(row, ks * 4 + lq));
+                }
+#pragma unroll
+                for (int j = 0; j < FN; j++) {
+                    int row = wn * TN + j * 16 + l16;
+                    fb[j] = *reinterpret_cast<const v8bf *>(lds_b + lds_off(row, ks * 4 + lq));
+                }
+#pragma unroll
+                for (int i = 0; i < FM; i++)
+#pragma unroll
+                    for (int j = 0; j < FN; j++)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+
+    // epilogue: one multiply by the product of the two FP32 scales (paper Fig. 3b)
+    const float scale = (MODE == kModeFp8Mx) ? (*a_s) * (*b_s) : 1.0f;
+    const bool vec_ok = (ld_out % 4 == 0);
+#pragma unroll
+    for (int i = 0; i < FM; i++) {
+        const int64_t m = m0 + wm * TM + i * 16 + l16;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < FN; j++) {
+            const int64_t n = n0 + wn * TN + j * 16 + 4 * lq;
+            if (n >= N) continue;
+            float r[4] = {acc[i][j][0] * scale, acc[i][j][1] * scale, acc[i][j][2] * scale, acc[i][j][3] * scale};
+            if (out_f32) {
+                float *o = reinterpret_cast<float *>(out) + m * ld_out + n;
+                if (vec_ok && n + 3 < N) {
+                    float4 v = make_float4(r[0], r[1], r[2], r[3]);
+                    if (accumulate) {
+                        float4 p = *reinterpret_cast<float4 *>(o);
+                        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+                    }
+                    *reinterpret_cast<float4 *>(o) = v;
+                } else {
+                    for (int t = 0; t < 4 && n + t < N; t++) o[t] = accumulate ? o[t] + r[t] : r[t];
+                }
+            } else {
+                uint16_t *o = reinterpret_cast<uint16_t *>(out) + m * ld_out + n;
+                if (vec_ok && n + 3 < N) {
+                    uint32_t lo = f32_to_bf16_rne(r[0]) | (f32_to_bf16_rne(r[1]) << 16);
+                    uint32_t hi = f32_to_bf16_rne(r[2]) | (f32_to_bf16_rne(r[3]) << 16);
+                    *reinterpret_cast<uint2 *>(o) = make_uint2(lo, hi);
+                } else {
+                    for (int t = 0; t < 4 && n + t < N; t++) o[t] = (uint16_t)f32_to_bf16_rne(r[t]);
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int MODE>
+static int launch_gemm(int64_t M, int64_t N, int64_t Kb, const uint8_t *a_q, const uint8_t *a_e, const float *a_s,
+                       const uint8_t *b_q, const uint8_t *b_e, const float *b_s, void *out, int out_f32,
+                       int64_t ld_out, int accumulate, hipStream_t st)
+{
+    const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    if (tiles_m * tiles_n > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
+    hipLaunchKernelGGL((k_gemm<BM, BN, WM, WN, MODE>), dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), 0, st, M, N,
+                       Kb, a_q, a_e, a_s, b_q, b_e, b_s, out, out_f32, ld_out, accumulate, (int)tiles_m, (int)tiles_n);
+    MOSS_LAUNCH_CHECK();
+    return MOSS_OK;
+}
+
+}  // namespace moss
+
+extern "C" size_t moss_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    (void)M; (void)N; (void)K;
+    return 0;
+}
+
+extern "C" int moss_gemm_fp8_mx(int64_t M, int64_t N, int64_t K,
+                                const uint8_t *a_q, const uint8_t *a_e, const float *a_s,
+                                const uint8_t *b_q, const uint8_t *b_e, const float *b_s,
+                                void *out, int out_dtype, int64_t ld_out, int accumulate,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace moss;
+    (void)workspace; (void)workspace_bytes;
+    if (!a_q || !b_q || !a_s || !b_s || !out) return MOSS_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || K % kGroup || ld_out < N) return MOSS_ERR_SHAPE;
+    if (out_dtype != MOSS_DT_BF16 && out_dtype != MOSS_DT_F32) return MOSS_ERR_UNSUPPORTED;
+    if (accumulate && out_dtype != MOSS_DT_F32) return MOSS_ERR_UNSUPPORTED;
+    if (!moss_aligned16(a_q) || !moss_aligned16(b_q) || !moss_aligned16(out)) return MOSS_ERR_ALIGN;
+    if (((uintptr_t)a_s & 3) || ((uintptr_t)b_s & 3)) return MOSS_ERR_ALIGN;
+    if (K % 16) return MOSS_ERR_ALIGN;
+    return launch_gemm<128, 128, 2, 2, kModeFp8Mx>(M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out, out_dtype == MOSS_DT_F32,
+                                                   ld_out, accumulate, (hipStream_t)stream);
+}
+
+extern "C" int moss_gemm_bf16_baseline(int64_t M, int64_t N, int64_t K, const void *a_bf16, const void *b_bf16,
+                                       void *out_bf16, int64_t ld_out, void *stream)
+{
+    using namespace moss;
+    if (!a_bf16 || !b_bf16 || !out_bf16) return MOSS_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || K % kGroup || ld_out < N) return MOSS_ERR_SHAPE;
+    if (!moss_aligned16(a_bf16) || !moss_aligned16(b_bf16) || !moss_aligned16(out_bf16)) return MOSS_ERR_ALIGN;
+    return launch_gemm<128, 128, 2, 2, kModeBf16>(M, N, 2 * K, (const uint8_t *)a_bf16, nullptr, nullptr,
+                                                  (const uint8_t *)b_bf16, nullptr, nullptr, out_bf16, 0, ld_out, 0,
+                                                  (hipStream_t)stream);
+}

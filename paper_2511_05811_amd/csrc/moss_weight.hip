@@ -1,0 +1,353 @@
+// Per-tensor FP8 weights with automatic scaling for gfx950 (paper Sec. 3.2, Eq. 6;
+// AdamW of Sec. 2.2 Eq. 3; App. C).
+//
+// The optimizer step is one streaming pass: each workgroup derives the predicted
+// scale s_t = s_base + cum_lr/448 from the device-resident state (O(1), no
+// max-reduction), applies AdamW to its slice, writes W, m, v and the E4M3 codes of the
+// new weights, and leaves one partial amax / clipped-element count per workgroup in
+// the workspace.  A one-workgroup epilogue kernel folds the partials into the state.
+// Partials instead of atomics keep the result independent of scheduling.
+#include "moss_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace moss {
+
+constexpr int kWThreads = 256;
+constexpr int kWMaxBlocks = 4096;
+
+struct WPartials {
+    float *amax;      // [kWMaxBlocks]
+    uint32_t *over;   // [kWMaxBlocks]
+};
+
+__device__ __forceinline__ WPartials ws_partials(void *ws)
+{
+    WPartials p;
+    p.amax = reinterpret_cast<float *>(ws);
+    p.over = reinterpret_cast<uint32_t *>(ws) + kWMaxBlocks;
+    return p;
+}
+
+// Block-wide max / sum; the result is valid in thread 0 only.
+__device__ __forceinline__ void block_reduce(float &amax, uint32_t &over)
+{
+    __shared__ float r_amax[kWThreads / kWave];
+    __shared__ uint32_t r_over[kWThreads / kWave];
+    amax = wave_max_f32(amax);
+    over = wave_sum_u32(over);
+    if ((threadIdx.x & 63) == 0) {
+        r_amax[threadIdx.x >> 6] = amax;
+        r_over[threadIdx.x >> 6] = over;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < kWThreads / kWave; i++) {
+            amax = fmaxf(amax, r_amax[i]);
+            over += r_over[i];
+        }
+    }
+}
+
+__device__ __forceinline__ void block_reduce_store(float amax, uint32_t over, void *ws)
+{
+    block_reduce(amax, over);
+    if (threadIdx.x == 0) {
+        WPartials p = ws_partials(ws);
+        p.amax[blockIdx.x] = amax;
+        p.over[blockIdx.x] = over;
+    }
+}
+
+__device__ __forceinline__ float4 load_as_f32x4(const void *p, int64_t i4, bool bf16)
+{
+    if (bf16) {
+        uint2 r = reinterpret_cast<const uint2 *>(p)[i4];
+        return make_float4(bf16_bits_to_f32(r.x & 0xFFFFu), __uint_as_float(r.x & 0xFFFF0000u),
+                           bf16_bits_to_f32(r.y & 0xFFFFu), __uint_as_float(r.y & 0xFFFF0000u));
+    }
+    return reinterpret_cast<const float4 *>(p)[i4];
+}
+
+struct AdamW {
+    float lr, beta1, beta2, eps, wd, omb1, omb2, bc1, bc2;
+};
+
+// One AdamW element update; every operation is a single correctly rounded FP32
+// operation in the order of Eq. 3 of the paper (no FMA contraction).
+__device__ __forceinline__ void adamw_elem(float &w, float &m, float &v, float g, const AdamW &a)
+{
+    float mi = a.beta1 * m + a.omb1 * g;
+    float vi = a.beta2 * v + (a.omb2 * g) * g;
+    float mhat = __fdiv_rn(mi, a.bc1);
+    float vhat = __fdiv_rn(vi, a.bc2);
+    float den = __fsqrt_rn(vhat) + a.eps;
+    float u = __fdiv_rn(mhat, den);
+    float upd = a.lr * (u + a.wd * w);
+    w = w - upd;
+    m = mi;
+    v = vi;
+}
+
+// Scale the cast of this call uses.  predict != 0: Eq. 6 from the state before the
+// step; predict == 0: the scale already stored in the state (after init / re-base).
+__device__ __forceinline__ float scale_for_cast(const moss_wscale_state *st, int predict, double lr_term)
+{
+    if (!predict) return st->s_cur;
+    double cum = st->cum_lr + lr_term;
+    return (float)((double)st->s_base + cum / 448.0);
+}
+
+template <bool G_BF16, bool DO_CAST>
+__global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w, float *__restrict__ m,
+                                                          float *__restrict__ v, const void *__restrict__ g,
+                                                          int64_t n4, AdamW a, double lr_term,
+                                                          const moss_wscale_state *__restrict__ st,
+                                                          uint8_t *__restrict__ wq, void *ws)
+{
+    float inv_s = 0.0f;
+    if (DO_CAST) {
+        float s = scale_for_cast(st, 1, lr_term);
+        inv_s = s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f;
+    }
+    float amax = 0.0f;
+    uint32_t over = 0;
+    const int64_t stride = (int64_t)gridDim.x * kWThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kWThreads + threadIdx.x; i < n4; i += stride) {
+        float4 wv = reinterpret_cast<float4 *>(w)[i];
+        float4 mv = reinterpret_cast<float4 *>(m)[i];
+        float4 vv = reinterpret_cast<float4 *>(v)[i];
+        float4 gv = load_as_f32x4(g, i, G_BF16);
+        adamw_elem(wv.x, mv.x, vv.x, gv.x, a);
+        adamw_elem(wv.y, mv.y, vv.y, gv.y, a);
+        adamw_elem(wv.z, mv.z, vv.z, gv.z, a);
+        adamw_elem(wv.w, mv.w, vv.w, gv.w, a);
+        reinterpret_cast<float4 *>(w)[i] = wv;
+        reinterpret_cast<float4 *>(m)[i] = mv;
+        reinterpret_cast<float4 *>(v)[i] = vv;
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+        if (DO_CAST) {
+            float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
+            over += (fabsf(y0) > kE4M3Max) + (fabsf(y1) > kE4M3Max) + (fabsf(y2) > kE4M3Max) + (fabsf(y3) > kE4M3Max);
+            reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
+        }
+    }
+    block_reduce_store(amax, over, ws);
+}
+
+template <bool W_BF16>
+__global__ __launch_bounds__(kWThreads) void k_weight_amax(const void *__restrict__ w, int64_t n4, void *ws)
+{
+    float amax = 0.0f;
+    const int64_t stride = (int64_t)gridDim.x * kWThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kWThreads + threadIdx.x; i < n4; i += stride) {
+        float4 wv = load_as_f32x4(w, i, W_BF16);
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+    }
+    block_reduce_store(amax, 0u, ws);
+}
+
+template <bool W_BF16>
+__global__ __launch_bounds__(kWThreads) void k_weight_cast(const void *__restrict__ w, int64_t n4,
+                                                           const moss_wscale_state *__restrict__ st,
+                                                           uint8_t *__restrict__ wq, void *ws)
+{
+    const float s = scale_for_cast(st, 0, 0.0);
+    const float inv_s = s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f;
+    float amax = 0.0f;
+    uint32_t over = 0;
+    const int64_t stride = (int64_t)gridDim.x * kWThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kWThreads + threadIdx.x; i < n4; i += stride) {
+        float4 wv = load_as_f32x4(w, i, W_BF16);
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+        float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
+        over += (fabsf(y0) > kE4M3Max) + (fabsf(y1) > kE4M3Max) + (fabsf(y2) > kE4M3Max) + (fabsf(y3) > kE4M3Max);
+        reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
+    }
+    block_reduce_store(amax, over, ws);
+}
+
+enum FinalizeMode {
+    kFinInit = 0,     // after k_weight_amax at initialisation: reset state, s_base = s_cur = amax/448
+    kFinStep = 1,     // after a fused step: advance step / cum_lr / s_cur, record amax, add overflow
+    kFinRebase = 2,   // after an AdamW-only pass on a re-scaling step: s_base = s_cur = amax/448
+    kFinCastOnly = 3  // after a cast-only pass: record amax, add overflow
+};
+
+__global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state *st, void *ws, int n_partial, int mode,
+                                                               double lr_term)
+{
+    WPartials p = ws_partials(ws);
+    float amax = 0.0f;
+    uint32_t over = 0;
+    for (int i = threadIdx.x; i < n_partial; i += kWThreads) {
+        amax = fmaxf(amax, p.amax[i]);
+        over += p.over[i];
+    }
+    block_reduce(amax, over);
+    if (threadIdx.x != 0) return;
+    if (mode == kFinInit) {
+        st->s_base = __fdiv_rn(amax, kE4M3Max);
+        st->s_cur = st->s_base;
+        st->cum_lr = 0.0;
+        st->step = 0;
+        st->last_rebase = 0;
+        st->amax_seen = amax;
+        st->overflow_count = 0;
+    } else if (mode == kFinStep) {
+        double cum = st->cum_lr + lr_term;
+        st->cum_lr = cum;
+        st->s_cur = (float)((double)st->s_base + cum / 448.0);
+        st->step += 1;
+        st->amax_seen = amax;
+        st->overflow_count += over;
+    } else if (mode == kFinRebase) {
+        st->step += 1;
+        st->s_base = __fdiv_rn(amax, kE4M3Max);
+        st->s_cur = st->s_base;
+        st->cum_lr = 0.0;
+        st->last_rebase = st->step;
+        st->amax_seen = amax;
+    } else {
+        st->amax_seen = amax;
+        st->overflow_count += over;
+    }
+}
+
+// Byte transpose [rows x cols] -> [cols x rows] through a padded LDS tile.
+constexpr int kTT = 64;
+__global__ __launch_bounds__(256) void k_transpose_u8(const uint8_t *__restrict__ src, int64_t rows, int64_t cols,
+                                                      uint8_t *__restrict__ dst)
+{
+    __shared__ uint8_t tile[kTT][kTT + 4];
+    const int64_t r0 = (int64_t)blockIdx.y * kTT, c0 = (int64_t)blockIdx.x * kTT;
+    for (int i = threadIdx.x; i < kTT * kTT; i += 256) {
+        int r = i / kTT, c = i % kTT;
+        if (r0 + r < rows && c0 + c < cols) tile[r][c] = src[(r0 + r) * cols + c0 + c];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kTT * kTT; i += 256) {
+        int c = i / kTT, r = i % kTT;
+        if (r0 + r < rows && c0 + c < cols) dst[(c0 + c) * rows + r0 + r] = tile[r][c];
+    }
+}
+
+static int grid_for(int64_t n4)
+{
+    int64_t per_block = (int64_t)kWThreads * 4;   // >= 4 vectors per thread before striding
+    int64_t blocks = (n4 + per_block - 1) / per_block;
+    if (blocks < 1) blocks = 1;
+    return (int)(blocks < kWMaxBlocks ? blocks : kWMaxBlocks);
+}
+
+static int launch_transpose(const uint8_t *src, int64_t rows, int64_t cols, uint8_t *dst, hipStream_t st)
+{
+    int64_t gx = (cols + kTT - 1) / kTT, gy = (rows + kTT - 1) / kTT;
+    if (gy > 65535) return MOSS_ERR_SHAPE;
+    hipLaunchKernelGGL(k_transpose_u8, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, src, rows, cols, dst);
+    MOSS_LAUNCH_CHECK();
+    return MOSS_OK;
+}
+
+}  // namespace moss
+
+extern "C" size_t moss_weight_workspace_bytes(int64_t rows, int64_t cols)
+{
+    (void)rows; (void)cols;
+    return (size_t)moss::kWMaxBlocks * (sizeof(float) + sizeof(uint32_t));
+}
+
+static int check_weight_common(int64_t rows, int64_t cols, const void *state, const void *wq, const void *wq_t,
+                               const void *ws, size_t ws_bytes)
+{
+    if (!state || !wq) return MOSS_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || (rows * cols) % 4) return MOSS_ERR_SHAPE;
+    if (!moss_aligned16(wq) || ((uintptr_t)state & 7)) return MOSS_ERR_ALIGN;
+    (void)wq_t;
+    if (!ws || ws_bytes < moss_weight_workspace_bytes(rows, cols)) return MOSS_ERR_WORKSPACE;
+    if (!moss_aligned16(ws)) return MOSS_ERR_ALIGN;
+    return MOSS_OK;
+}
+
+extern "C" int moss_weight_autoscale_init(const void *w, int w_dtype, int64_t rows, int64_t cols,
+                                          moss_wscale_state *state, uint8_t *wq, uint8_t *wq_t,
+                                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace moss;
+    if (!w) return MOSS_ERR_NULL;
+    if (w_dtype != MOSS_DT_F32 && w_dtype != MOSS_DT_BF16) return MOSS_ERR_UNSUPPORTED;
+    int rc = check_weight_common(rows, cols, state, wq, wq_t, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!moss_aligned16(w)) return MOSS_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n4 = rows * cols / 4;
+    const int grid = grid_for(n4);
+    if (w_dtype == MOSS_DT_BF16)
+        hipLaunchKernelGGL(k_weight_amax<true>, dim3(grid), dim3(kWThreads), 0, st, w, n4, workspace);
+    else
+        hipLaunchKernelGGL(k_weight_amax<false>, dim3(grid), dim3(kWThreads), 0, st, w, n4, workspace);
+    MOSS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinInit, 0.0);
+    MOSS_LAUNCH_CHECK();
+    if (w_dtype == MOSS_DT_BF16)
+        hipLaunchKernelGGL(k_weight_cast<true>, dim3(grid), dim3(kWThreads), 0, st, w, n4, state, wq, workspace);
+    else
+        hipLaunchKernelGGL(k_weight_cast<false>, dim3(grid), dim3(kWThreads), 0, st, w, n4, state, wq, workspace);
+    MOSS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinCastOnly, 0.0);
+    MOSS_LAUNCH_CHECK();
+    if (wq_t) return launch_transpose(wq, rows, cols, wq_t, st);
+    return MOSS_OK;
+}
+
+extern "C" int moss_weight_autoscale_cast(float *w, float *m, float *v, const void *g, int g_dtype,
+                                          int64_t rows, int64_t cols, const moss_adamw_args *args,
+                                          moss_wscale_state *state, uint8_t *wq, uint8_t *wq_t,
+                                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace moss;
+    if (!w || !m || !v || !g || !args) return MOSS_ERR_NULL;
+    if (g_dtype != MOSS_DT_F32 && g_dtype != MOSS_DT_BF16) return MOSS_ERR_UNSUPPORTED;
+    int rc = check_weight_common(rows, cols, state, wq, wq_t, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!moss_aligned16(w) || !moss_aligned16(m) || !moss_aligned16(v) || ((uintptr_t)g & 7)) return MOSS_ERR_ALIGN;
+    if (g_dtype == MOSS_DT_F32 && !moss_aligned16(g)) return MOSS_ERR_ALIGN;
+    if (args->step < 1) return MOSS_ERR_SHAPE;
+
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n4 = rows * cols / 4;
+    const int grid = grid_for(n4);
+    AdamW a{args->lr, args->beta1, args->beta2, args->eps, args->weight_decay,
+            args->one_minus_beta1, args->one_minus_beta2, args->bias_corr1, args->bias_corr2};
+    const double lr_term = (double)args->margin * (double)args->lr;
+    const bool rebase = args->interval > 0 && (args->step % args->interval) == 0;
+    const bool gb = g_dtype == MOSS_DT_BF16;
+
+    if (!rebase) {
+        if (gb)
+            hipLaunchKernelGGL((k_adamw_cast<true, true>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
+                               state, wq, workspace);
+        else
+            hipLaunchKernelGGL((k_adamw_cast<false, true>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
+                               state, wq, workspace);
+        MOSS_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinStep, lr_term);
+        MOSS_LAUNCH_CHECK();
+    } else {
+        if (gb)
+            hipLaunchKernelGGL((k_adamw_cast<true, false>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
+                               state, wq, workspace);
+        else
+            hipLaunchKernelGGL((k_adamw_cast<false, false>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
+                               state, wq, workspace);
+        MOSS_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinRebase, lr_term);
+        MOSS_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_weight_cast<false>, dim3(grid), dim3(kWThreads), 0, st, (const void *)w, n4, state, wq, workspace);
+        MOSS_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinCastOnly, 0.0);
+        MOSS_LAUNCH_CHECK();
+    }
+    if (wq_t) return launch_transpose(wq, rows, cols, wq_t, st);
+    return MOSS_OK;
+}

@@ -1,0 +1,106 @@
+"""GPU parity of moss_quant_act_2level against the CPU oracle: bit-exact codes,
+exponent bytes and global scale (paper Sec. 3.1, Eq. 1-2)."""
+import numpy as np
+import pytest
+import torch
+
+import moss_inputs as mi
+import paper_2511_05811_amd as moss
+from gpu_util import bf16_to_gpu, scalar, u8
+
+pytestmark = pytest.mark.gpu
+
+ROW, COL, CEIL = moss.MOSS_Q_ROW, moss.MOSS_Q_COL, moss.MOSS_EXP_CEIL
+
+
+def check_against_oracle(oracle, xb, mode_flag, tag, x_dev=None):
+    print(f"[quant parity] {tag} shape={xb.shape} mode={'ceil' if mode_flag else 'nearest'}", flush=True)
+    x = bf16_to_gpu(xb) if x_dev is None else x_dev
+    mode = 1 if mode_flag else 0
+    qr, er, sr = oracle.quant_act_2level(xb, 0, mode)
+    got = moss.quant_act_2level(x, ROW | mode_flag)
+    torch.cuda.synchronize()
+    assert scalar(got["s"]) == sr, tag
+    assert np.array_equal(u8(got["e_row"]), er), tag
+    assert np.array_equal(u8(got["q_row"]), qr), tag
+    if xb.shape[0] % 32 == 0:
+        qc, ec, sc = oracle.quant_act_2level(xb, 1, mode)
+        got = moss.quant_act_2level(x, COL | mode_flag)
+        torch.cuda.synchronize()
+        assert scalar(got["s"]) == sc == sr, tag
+        assert np.array_equal(u8(got["e_col"]), ec), tag
+        assert np.array_equal(u8(got["q_col"]), qc), tag
+        both = moss.quant_act_2level(x, ROW | COL | mode_flag)
+        torch.cuda.synchronize()
+        assert scalar(both["s"]) == sr
+        assert np.array_equal(u8(both["q_row"]), qr) and np.array_equal(u8(both["e_row"]), er)
+        assert np.array_equal(u8(both["q_col"]), qc) and np.array_equal(u8(both["e_col"]), ec)
+
+
+def test_every_bf16_value_through_the_converter(oracle):
+    # all finite BF16 bit patterns up to 2^20 in magnitude (including subnormals and both
+    # zeros), laid out so that groups mix magnitudes; larger patterns are replaced by zero
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    ex = (bits >> 7) & 0xFF
+    bits[ex > 127 + 20] = 0
+    rng = np.random.default_rng(3)
+    xb = rng.permutation(bits).reshape(64, 1024)
+    for flag in (0, CEIL):
+        check_against_oracle(oracle, xb, flag, "all-bf16 shuffled")
+    # sorted layout: neighbouring values share a group, so every code of the E4M3 grid and
+    # many exact rounding ties are hit
+    check_against_oracle(oracle, np.sort(bits).reshape(64, 1024), 0, "all-bf16 sorted")
+
+
+def test_config1_activation(oracle):
+    xb, _ = mi.config1()
+    for flag in (0, CEIL):
+        check_against_oracle(oracle, xb, flag, "config1 X")
+
+
+@pytest.mark.parametrize("name", ["zeros", "zero_groups", "one_outlier", "signed_zeros", "tiny", "big",
+                                  "sqrt2_boundary", "wide_range"])
+def test_adversarial_tensors(oracle, name):
+    xb = mi.adversarial_activations(64, 128)[name]
+    for flag in (0, CEIL):
+        check_against_oracle(oracle, xb, flag, name)
+
+
+@pytest.mark.parametrize("shape", [(32, 32), (1, 32), (7, 96), (96, 160), (33, 4096), (1056, 1184), (2080, 32)])
+def test_ragged_shapes(oracle, shape):
+    xb = mi.heavy_tailed_activation(shape[0], shape[1], seed=20 + shape[0])
+    check_against_oracle(oracle, xb, 0, f"ragged {shape}")
+
+
+def test_row_stride_larger_than_cols(oracle):
+    xb_full = mi.heavy_tailed_activation(96, 256, seed=31)
+    x_full = bf16_to_gpu(xb_full)
+    x_view = x_full[:, 64:224]                     # ld = 256, cols = 160, 16-byte aligned start
+    xb = np.ascontiguousarray(xb_full[:, 64:224])
+    check_against_oracle(oracle, xb, 0, "strided view", x_dev=x_view)
+
+
+def test_config2_full_size(oracle):
+    xb = mi.config2()
+    assert xb.shape == (8192, 4096)
+    check_against_oracle(oracle, xb, 0, "config2 full")
+
+
+def test_outputs_are_written_exactly_once_into_caller_buffers(oracle):
+    # poison the output buffers: every byte must be overwritten, nothing beyond them touched
+    xb = mi.heavy_tailed_activation(96, 160, seed=33)
+    x = bf16_to_gpu(xb)
+    d = x.device
+    pad = 64
+    bufs = {k: torch.full((n + 2 * pad,), 0xAB, dtype=torch.uint8, device=d)
+            for k, n in dict(q_row=96 * 160, e_row=96 * 5, q_col=96 * 160, e_col=160 * 3).items()}
+    out = dict(q_row=bufs["q_row"][pad:-pad].view(96, 160), e_row=bufs["e_row"][pad:-pad].view(96, 5),
+               q_col=bufs["q_col"][pad:-pad].view(160, 96), e_col=bufs["e_col"][pad:-pad].view(160, 3))
+    got = moss.quant_act_2level(x, ROW | COL, out=out)
+    torch.cuda.synchronize()
+    qr, er, s = oracle.quant_act_2level(xb, 0, 0)
+    qc, ec, _ = oracle.quant_act_2level(xb, 1, 0)
+    assert np.array_equal(u8(got["q_row"]), qr) and np.array_equal(u8(got["e_row"]), er)
+    assert np.array_equal(u8(got["q_col"]), qc) and np.array_equal(u8(got["e_col"]), ec)
+    for b in bufs.values():
+        assert (b[:pad] == 0xAB).all() and (b[-pad:] == 0xAB).all()
