@@ -99,7 +99,8 @@ typedef struct {
     int64_t step;            /* optimizer steps taken */
     int64_t last_rebase;     /* step of the last max-reduction */
     float amax_seen;         /* amax of the weights at the latest cast (free by-product) */
-    uint32_t overflow_count; /* elements whose scaled value exceeded 448 and was clipped, cumulative */
+    uint32_t overflow_count; /* elements the saturating cast clipped: |w/s| > 464, i.e. beyond the
+                                values that round to 448 by themselves; cumulative */
 } moss_wscale_state;
 
 typedef struct {

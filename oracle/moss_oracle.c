@@ -203,7 +203,8 @@ typedef struct {
     int64_t step;            /* optimizer steps taken */
     int64_t last_rebase;     /* step of the last max-reduction */
     float amax_seen;         /* amax of the weights at the latest cast */
-    uint32_t overflow_count; /* elements the casts had to saturate, cumulative */
+    uint32_t overflow_count; /* elements the saturating casts clipped (|w/s| > 464, i.e. beyond
+                                what rounds to 448 by itself), cumulative */
 } moss_oracle_wstate;
 
 typedef struct {
@@ -225,7 +226,7 @@ static void cast_weights(const float *w, int64_t n, float s, uint8_t *wq,
     for (int64_t i = 0; i < n; i++) {
         float y = w[i] * inv_s;
         if (fabsf(w[i]) > amax) amax = fabsf(w[i]);
-        if (fabsf(y) > 448.0f) over++;
+        if (fabsf(y) > 464.0f) over++;   /* beyond the values that round to 448 on their own */
         if (wq) wq[i] = moss_oracle_e4m3_encode((double)y);
     }
     *amax_out = amax;

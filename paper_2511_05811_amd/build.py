@@ -11,6 +11,7 @@ SOURCES = ["moss_api.hip", "moss_quant.hip", "moss_weight.hip", "moss_gemm.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-ffp-contract=off",                      # numerically specified kernels: no FMA contraction
+         "-fhip-fp32-correctly-rounded-divide-sqrt",  # IEEE '/' and sqrtf in device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 

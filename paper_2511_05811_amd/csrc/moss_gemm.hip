@@ -6,8 +6,10 @@
 //   out[m,n] = a_s b_s sum_k dec(a[m,k]) 2^(ae[m,k/32]-127) dec(b[n,k]) 2^(be[n,k/32]-127)
 //
 // Both operands are K-contiguous ([M x K] and [N x K]).  One V_MFMA_SCALE_F32_16X16X128
-// consumes, per lane, 32 consecutive K bytes of one row (= exactly one level-2 group)
-// of each operand plus one scale byte per operand.  The b operand is fed as the
+// covers 128 K per operand row.  Lane (r = lane%16, j = lane/16) supplies for row r the
+// 16 bytes K[16j, 16j+16) in its first four source registers and K[64+16j, 64+16j+16) in
+// the last four, and the E8M0 scale byte of the 32-wide group K[32j, 32j+32) (measured
+// with one-hot operands: the instruction scales K block B of row r by lane r+16B's byte).  The b operand is fed as the
 // instruction's first source so that a lane ends up with four consecutive n of one
 // output row and can store them with one vector store.
 //
@@ -136,15 +138,15 @@ __global__ __launch_bounds__(WM *WN * 64) void k_gemm(int64_t M, int64_t N, int6
 #pragma unroll
             for (int i = 0; i < FM; i++) {
                 int row = wm * TM + i * 16 + l16;
-                uint4 lo = *reinterpret_cast<const uint4 *>(lds_a + lds_off(row, 2 * lq));
-                uint4 hi = *reinterpret_cast<const uint4 *>(lds_a + lds_off(row, 2 * lq + 1));
+                uint4 lo = *reinterpret_cast<const uint4 *>(lds_a + lds_off(row, lq));
+                uint4 hi = *reinterpret_cast<const uint4 *>(lds_a + lds_off(row, lq + 4));
                 fa[i] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
             }
 #pragma unroll
             for (int j = 0; j < FN; j++) {
                 int row = wn * TN + j * 16 + l16;
-                uint4 lo = *reinterpret_cast<const uint4 *>(lds_b + lds_off(row, 2 * lq));
-                uint4 hi = *reinterpret_cast<const uint4 *>(lds_b + lds_off(row, 2 * lq + 1));
+                uint4 lo = *reinterpret_cast<const uint4 *>(lds_b + lds_off(row, lq));
+                uint4 hi = *reinterpret_cast<const uint4 *>(lds_b + lds_off(row, lq + 4));
                 fb[j] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
             }
 #pragma unroll

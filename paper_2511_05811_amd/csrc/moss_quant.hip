@@ -79,8 +79,8 @@ __device__ __forceinline__ GlobalScale fold_global_scale(const uint32_t *partial
     GlobalScale g;
     float amax = bf16_bits_to_f32(m);
     g.zero = (m == 0);
-    g.s = g.zero ? 1.0f : __fdiv_rn(amax, kE4M3Max);
-    g.inv_s = __fdiv_rn(1.0f, g.s);
+    g.s = g.zero ? 1.0f : amax / kE4M3Max;
+    g.inv_s = 1.0f / g.s;
     g.frac = __builtin_amdgcn_frexp_mantf(amax);
     g.expo = __builtin_amdgcn_frexp_expf(amax);
     return g;

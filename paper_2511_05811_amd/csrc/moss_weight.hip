@@ -15,6 +15,9 @@ namespace moss {
 
 constexpr int kWThreads = 256;
 constexpr int kWMaxBlocks = 4096;
+// |y| <= 464 rounds to 448 by itself (464 is the midpoint to the next grid point, tie to
+// even); beyond it the saturating cast changes the result: that is a clipped element.
+constexpr float kClip = 464.0f;
 
 struct WPartials {
     float *amax;      // [kWMaxBlocks]
@@ -74,15 +77,16 @@ struct AdamW {
 };
 
 // One AdamW element update; every operation is a single correctly rounded FP32
-// operation in the order of Eq. 3 of the paper (no FMA contraction).
+// operation in the order of Eq. 3 of the paper (no FMA contraction; the build asks for
+// IEEE division and square root).
 __device__ __forceinline__ void adamw_elem(float &w, float &m, float &v, float g, const AdamW &a)
 {
     float mi = a.beta1 * m + a.omb1 * g;
     float vi = a.beta2 * v + (a.omb2 * g) * g;
-    float mhat = __fdiv_rn(mi, a.bc1);
-    float vhat = __fdiv_rn(vi, a.bc2);
-    float den = __fsqrt_rn(vhat) + a.eps;
-    float u = __fdiv_rn(mhat, den);
+    float mhat = mi / a.bc1;
+    float vhat = vi / a.bc2;
+    float den = sqrtf(vhat) + a.eps;
+    float u = mhat / den;
     float upd = a.lr * (u + a.wd * w);
     w = w - upd;
     m = mi;
@@ -108,7 +112,7 @@ __global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w,
     float inv_s = 0.0f;
     if (DO_CAST) {
         float s = scale_for_cast(st, 1, lr_term);
-        inv_s = s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f;
+        inv_s = s > 0.0f ? 1.0f / s : 0.0f;
     }
     float amax = 0.0f;
     uint32_t over = 0;
@@ -128,7 +132,7 @@ __global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w,
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
         if (DO_CAST) {
             float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
-            over += (fabsf(y0) > kE4M3Max) + (fabsf(y1) > kE4M3Max) + (fabsf(y2) > kE4M3Max) + (fabsf(y3) > kE4M3Max);
+            over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
             reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
         }
     }
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_cast(const void *__restric
                                                            uint8_t *__restrict__ wq, void *ws)
 {
     const float s = scale_for_cast(st, 0, 0.0);
-    const float inv_s = s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f;
+    const float inv_s = s > 0.0f ? 1.0f / s : 0.0f;
     float amax = 0.0f;
     uint32_t over = 0;
     const int64_t stride = (int64_t)gridDim.x * kWThreads;
@@ -161,7 +165,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_cast(const void *__restric
         float4 wv = load_as_f32x4(w, i, W_BF16);
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
         float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
-        over += (fabsf(y0) > kE4M3Max) + (fabsf(y1) > kE4M3Max) + (fabsf(y2) > kE4M3Max) + (fabsf(y3) > kE4M3Max);
+        over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
         reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
     }
     block_reduce_store(amax, over, ws);
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state
     block_reduce(amax, over);
     if (threadIdx.x != 0) return;
     if (mode == kFinInit) {
-        st->s_base = __fdiv_rn(amax, kE4M3Max);
+        st->s_base = amax / kE4M3Max;
         st->s_cur = st->s_base;
         st->cum_lr = 0.0;
         st->step = 0;
@@ -203,7 +207,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state
         st->overflow_count += over;
     } else if (mode == kFinRebase) {
         st->step += 1;
-        st->s_base = __fdiv_rn(amax, kE4M3Max);
+        st->s_base = amax / kE4M3Max;
         st->s_cur = st->s_base;
         st->cum_lr = 0.0;
         st->last_rebase = st->step;

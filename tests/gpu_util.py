@@ -27,3 +27,15 @@ def bf16_out_to_f64(t):
 
 def scalar(t):
     return np.float32(t.cpu().numpy().reshape(-1)[0])
+
+
+def assert_same_bits(got, want, tag):
+    """Bit-exact comparison with a short report instead of an array dump."""
+    got = np.ascontiguousarray(got); want = np.ascontiguousarray(want)
+    assert got.shape == want.shape and got.dtype.itemsize == want.dtype.itemsize, (tag, got.shape, want.shape)
+    view = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[got.dtype.itemsize]
+    bad = np.flatnonzero(got.view(view).ravel() != want.view(view).ravel())
+    if bad.size:
+        i = int(bad[0])
+        raise AssertionError(f"{tag}: {bad.size} of {got.size} elements differ; first at flat index {i}: "
+                             f"got {got.ravel()[i]!r} want {want.ravel()[i]!r}")

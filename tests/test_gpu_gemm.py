@@ -1,7 +1,7 @@
 """GPU parity of moss_gemm_fp8_mx (and of the whole quantize -> cast -> GEMM chain)
 against the CPU oracle's dequantize-then-FP64 GEMM (paper Sec. 3.1, Fig. 3b).
-Tolerance: |gpu - oracle| <= 1e-3 * |a_row|_2 * |b_row|_2 per output; BF16 outputs
-must also sit within one BF16 rounding step of the oracle value."""
+Tolerance: |gpu - oracle| <= 1e-3 * |a_row|_2 * |b_row|_2 per output for FP32 outputs;
+BF16 outputs get the same bound plus one rounding step of the BF16 output format."""
 import numpy as np
 import pytest
 import torch
@@ -33,11 +33,18 @@ def assert_close(got, ref, na, nb, bf16, tag):
     err = np.abs(got - ref)
     worst = float((err / np.maximum(tol / REL, 1e-300)).max())
     print(f"[gemm parity] {tag}: max |err| / (|a||b|) = {worst:.3e}", flush=True)
-    assert (err <= tol + 1e-30).all(), tag
     if bf16:
-        assert (err <= 2.0 ** -8 * np.abs(ref) + 1e-5 * tol / REL + 1e-30).all(), tag
+        # the bar applies to the FP32-accumulated result; storing it as BF16 adds one rounding of
+        # the output format (at most 2^-8 |y|), which alone can exceed 1e-3 |a||b| when a and b
+        # are nearly parallel
+        assert (err <= tol + 2.0 ** -8 * np.abs(ref) + 1e-30).all(), tag
+        assert (err <= 2.0 ** -8 * np.abs(ref) + 1e-4 * tol / REL + 1e-30).all(), tag
     else:
-        assert (err <= 2e-5 * tol / REL + 1e-30).all(), tag
+        assert (err <= tol + 1e-30).all(), tag
+        # tighter than the bar, to notice regressions: the matrix instruction sums each run of
+        # 16 products in a fixed-point window about 14 bits below the largest of them
+        # (measured), so wide-range random codes sit near 4e-5, quantized data near 1e-6
+        assert (err <= 1e-4 * tol / REL + 1e-30).all(), tag
 
 
 @pytest.mark.parametrize("shape", [(16, 16, 32), (1, 1, 32), (5, 3, 64), (128, 128, 128), (200, 136, 96),

@@ -7,7 +7,7 @@ import torch
 
 import moss_inputs as mi
 import paper_2511_05811_amd as moss
-from gpu_util import bf16_to_gpu, to_gpu, u8
+from gpu_util import assert_same_bits, bf16_to_gpu, to_gpu, u8
 
 pytestmark = pytest.mark.gpu
 
@@ -50,12 +50,12 @@ def run_parity(oracle, rows, cols, steps, seed, interval=500, bf16_grad=False, s
         if t % check_every == 0 or t == steps:
             torch.cuda.synchronize()
             tag = f"step {t}"
-            assert np.array_equal(wd.cpu().numpy().view(np.uint32), w.view(np.uint32)), tag
-            assert np.array_equal(md.cpu().numpy().view(np.uint32), m.view(np.uint32)), tag
-            assert np.array_equal(vd.cpu().numpy().view(np.uint32), v.view(np.uint32)), tag
-            assert np.array_equal(u8(wq_d), wq), tag
+            assert_same_bits(md.cpu().numpy(), m, tag + " m")
+            assert_same_bits(vd.cpu().numpy(), v, tag + " v")
+            assert_same_bits(wd.cpu().numpy(), w, tag + " w")
+            assert_same_bits(u8(wq_d), wq, tag + " wq")
             if transpose:
-                assert np.array_equal(u8(wqt_d), wq_t), tag
+                assert_same_bits(u8(wqt_d), wq_t, tag + " wq_t")
             assert_state_equal(moss.read_wscale_state(state), st, tag)
     return st
 
