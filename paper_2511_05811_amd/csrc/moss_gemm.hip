@@ -255,6 +255,13 @@ extern "C" int moss_gemm_fp8_mx(int64_t M, int64_t N, int64_t K,
     if (!moss_aligned16(a_q) || !moss_aligned16(b_q) || !moss_aligned16(out)) return MOSS_ERR_ALIGN;
     if (((uintptr_t)a_s & 3) || ((uintptr_t)b_s & 3)) return MOSS_ERR_ALIGN;
     if (K % 16) return MOSS_ERR_ALIGN;
+    // large problems: 256 x 256 tiles fed by direct global->LDS copies; everything else
+    // (small or odd shapes, missing a-side exponents) goes through the general kernel
+    if (((M + 255) / 256) * ((N + 255) / 256) >= 8 && a_e && !((uintptr_t)a_e & 3) && !(b_e && ((uintptr_t)b_e & 3))) {
+        int rc = moss_internal_gemm_big(M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out, out_dtype == MOSS_DT_F32, ld_out,
+                                        accumulate, (hipStream_t)stream);
+        if (rc != MOSS_ERR_UNSUPPORTED) return rc;
+    }
     return launch_gemm<128, 128, 2, 2, kModeFp8Mx>(M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out, out_dtype == MOSS_DT_F32,
                                                    ld_out, accumulate, (hipStream_t)stream);
 }

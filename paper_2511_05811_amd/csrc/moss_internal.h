@@ -22,6 +22,12 @@ static inline bool moss_aligned16(const void *p) { return (reinterpret_cast<uint
 
 int moss_internal_cu_count();
 
+// 256 x 256 tile fast path of the block-scaled GEMM; MOSS_ERR_UNSUPPORTED if the shape or
+// operands do not qualify (the caller falls back to the general kernel).
+int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, const uint8_t *a_e, const float *a_s,
+                           const uint8_t *b_q, const uint8_t *b_e, const float *b_s, void *out, int out_f32,
+                           int64_t ld_out, int accumulate, hipStream_t st);
+
 namespace moss {
 
 constexpr int kWave = 64;
