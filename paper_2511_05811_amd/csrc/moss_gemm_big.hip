@@ -5,26 +5,36 @@
 // Shape of the kernel
 //  * 256 x 256 output tile per workgroup of 4 waves (2 x 2), 128 x 128 per wave held as
 //    4 x 4 accumulators of V_MFMA_SCALE_F32_32X32X64_F8F6F4 (256 accumulator registers).
-//  * K advances in stages of 64 bytes.  A ring of four LDS stages (32 KiB each: 256 rows
-//    of a and 256 rows of b) is filled by direct global->LDS loads that never touch
-//    registers, issued three stages ahead of the stage being multiplied.
-//  * Fragments are double buffered in registers: while the 16 matrix instructions of
-//    stage t run, the fragments of stage t+1 are read from LDS.
-//  * One barrier per stage.  Before it each wave waits until all of its loads except the
-//    ones issued during this stage have landed (s_waitcnt vmcnt), so after the barrier
-//    stages <= t+2 are visible to every wave.
-//  * E8M0 scale bytes travel the same way: one dword (4 groups = 128 K) per row and
-//    stage pair, copied to a small LDS ring and read back as one register per fragment.
+//  * K advances in stages of 128 bytes = one full 128-byte cache line per tile row.  (The
+//    texture path costs about the same per line touched whether 64 or 128 bytes of it are
+//    used: 64-byte rows cap the feed rate near 27 B/clk/CU, full lines reach ~62, and the
+//    kernel needs 32 B/clk/CU at full matrix-core rate.)
+//  * Two LDS stage slots of 64 KiB (256 rows of a, 256 rows of b) filled by direct
+//    global->LDS loads that never touch registers.  A stage is multiplied in two substeps
+//    of K = 64; fragments are double buffered in registers, so the fragments of the next
+//    substep are read from LDS while the 16 matrix instructions of the current one run.
+//  * The loads of stage P+2 are issued at the start of substep 1 of stage P (their slot is
+//    free from then on) and have to land by the end of substep 0 of stage P+1: two
+//    substeps (2 x 1024 matrix-core cycles) of latency hiding with 64 KiB in flight.
+//  * One barrier per stage, at the end of substep 0; before it every wave waits for its
+//    own outstanding loads (stage P+1) and LDS reads.
+//  * E8M0 scale bytes travel the same way in blocks of 16 bytes (16 groups = K 512) per
+//    row into a small LDS ring; a lane reads one dword per fragment and stage and the
+//    instruction's byte selector picks the group of the substep.
+//  * Epilogue: accumulators times s_a*s_b are staged through LDS (row stride padded by 16
+//    bytes) so that every global store instruction writes whole 256-byte row pieces.
 //
 // Operand layout of the instruction (measured with one-hot operands): lane (r = lane%32,
 // h = lane/32) supplies for row r the bytes K[16h, 16h+16) in its first four source
 // registers and K[32+16h, 32+16h+16) in the last four; K block B (32 wide) of row r is
 // scaled by the selected byte of lane r+32B's scale register.
 //
-// LDS stage layout: row r = 64 bytes = four 16-byte chunks, chunk c stored at slot
-// c ^ ((r >> 2) & 3): the 16 rows a quarter-wave reads with one 16-byte access then hit
+// LDS stage layout: row r = 128 bytes = eight 16-byte chunks, chunk c stored at slot
+// c ^ ((r >> 1) & 7): the 16 rows a quarter-wave reads with one 16-byte access then hit
 // 16 different 16-byte bank groups, and a wave-wide global->LDS load still writes 1 KiB
-// of consecutive LDS (16 rows) while each lane fetches the chunk that belongs there.
+// of consecutive LDS (8 rows) while each lane fetches the chunk that belongs there.
+#include <type_traits>
+
 #include "moss_internal.h"
 
 namespace moss {
@@ -33,13 +43,14 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kBT = 256;                     // tile edge (rows of a and rows of b per workgroup)
-constexpr int kStageK = 64;                  // bytes of K per stage
-constexpr int kStages = 4;
-constexpr int kStageBytes = 2 * kBT * kStageK;        // a then b: 32 KiB
-constexpr int kScaleSlotBytes = 2 * kBT * 4;          // a then b: one dword per row
-constexpr int kScaleSlots = 4;
-constexpr int kScaleBase = kStages * kStageBytes;     // 128 KiB
-constexpr int kBigLdsBytes = kScaleBase + kScaleSlots * kScaleSlotBytes;   // 136 KiB
+constexpr int kStageK = 128;                 // bytes of K per stage (one cache line per row)
+constexpr int kSlotBytes = 2 * kBT * kStageK;          // a then b: 64 KiB
+constexpr int kScaleSlotBytes = 2 * kBT * 16;          // a then b, 16 exponent bytes (K 512) per row: 8 KiB
+constexpr int kScaleBase = 2 * kSlotBytes;             // 128 KiB
+constexpr int kBigLdsBytes = kScaleBase + 2 * kScaleSlotBytes;   // 144 KiB
+constexpr int kEpiRowBytes = 256 + 16;       // 128 BF16 (or 64 FP32) of one row + padding (keeps 16-byte alignment)
+constexpr int kEpiWaveBytes = 128 * kEpiRowBytes;      // 34 KiB per wave, 136 KiB in all
+static_assert(4 * kEpiWaveBytes <= kBigLdsBytes, "epilogue staging must fit");
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t big_smem[];
 
@@ -50,19 +61,15 @@ __device__ __forceinline__ void dma16(const uint8_t *base, uint32_t off, uint32_
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
 }
-__device__ __forceinline__ void dma4(const uint8_t *base, uint32_t off, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
-                 :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
-}
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-__device__ __forceinline__ void stage_barrier()
+__device__ __forceinline__ void wait_lds_and_barrier()
 {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
@@ -86,7 +93,6 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                                                         void *__restrict__ out, int out_f32, int64_t ld_out, int accumulate,
                                                         int tiles_m, int tiles_n)
 {
-    constexpr int NSC = HAS_BE ? 2 : 1;   // scale copies per stage pair and wave
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
@@ -99,11 +105,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     const int total = tiles_m * tiles_n;
     int pid = blockIdx.x;
     {
-        const int per = (total + 7) >> 3, xcd = pid & 7, idx = pid >> 3;
-        const int full = total - (per - 1) * 8;          // XCDs that own `per` tiles (others per-1)
-        int start = xcd < full ? xcd * per : full * per + (xcd - full) * (per - 1);
-        if (total % 8 == 0) start = xcd * per;
-        pid = start + idx;
+        const int q = total >> 3, r = total & 7, xcd = pid & 7, idx = pid >> 3;
+        pid = (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + idx;
     }
     constexpr int GM = 4;
     const int band = pid / (GM * tiles_n), rem = pid % (GM * tiles_n);
@@ -115,20 +118,20 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     const int64_t m0 = (int64_t)tm * kBT, n0 = (int64_t)tn * kBT;
 
     // ---- global -> LDS copy plan: per stage a wave copies 64 rows of a and 64 rows of b in
-    // four + four wave-wide 16-byte copies of 16 rows each
+    // eight + eight wave-wide copies of 8 full rows (8 x 128 B = 1 KiB of LDS) each
     const int G = (int)(K >> 5);
-    uint32_t a_off[4], b_off[4];
+    uint32_t a_off[8], b_off[8];
 #pragma unroll
-    for (int s = 0; s < 4; s++) {
-        const int r = wave * 64 + s * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((r >> 2) & 3);
+    for (int s = 0; s < 8; s++) {
+        const int r = wave * 64 + s * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
         int64_t ra = m0 + r, rb = n0 + r;
         ra = (ra < M ? ra : M - 1) - m0;
         rb = (rb < N ? rb : N - 1) - n0;
         a_off[s] = (uint32_t)(ra * K + c * 16);
         b_off[s] = (uint32_t)(rb * K + c * 16);
     }
-    uint32_t ae_off, be_off;
+    uint32_t ae_off, be_off;   // scale copies: lane = row, 16 bytes of that row's exponent bytes
     {
         const int r = wave * 64 + lane;
         int64_t ra = m0 + r, rb = n0 + r;
@@ -140,51 +143,62 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     const uint8_t *a_base = a_q + m0 * K, *b_base = b_q + n0 * K;
     const uint8_t *ae_base = a_e + m0 * G, *be_base = HAS_BE ? b_e + n0 * G : nullptr;
 
-    auto issue_stage = [&](int u) {   // u = stage index (wave-uniform)
-        const uint32_t slot = lds0 + (uint32_t)(u & (kStages - 1)) * kStageBytes + (uint32_t)wave * 64 * kStageK;
-        const uint8_t *ab = a_base + (int64_t)u * kStageK, *bb = b_base + (int64_t)u * kStageK;
+    auto issue_stage = [&](int P) {   // P = stage index (wave-uniform)
+        const uint32_t slot = lds0 + (uint32_t)(P & 1) * kSlotBytes + (uint32_t)wave * 64 * kStageK;
+        const uint8_t *ab = a_base + (int64_t)P * kStageK, *bb = b_base + (int64_t)P * kStageK;
 #pragma unroll
-        for (int s = 0; s < 4; s++) dma16(ab, a_off[s], slot + s * 16 * kStageK);
+        for (int s = 0; s < 8; s++) dma16(ab, a_off[s], slot + s * 8 * kStageK);
 #pragma unroll
-        for (int s = 0; s < 4; s++) dma16(bb, b_off[s], slot + kBT * kStageK + s * 16 * kStageK);
+        for (int s = 0; s < 8; s++) dma16(bb, b_off[s], slot + kBT * kStageK + s * 8 * kStageK);
     };
-    auto issue_scales = [&](int p) {  // p = stage-pair index: groups 4p .. 4p+3 of every row
-        const uint32_t slot = lds0 + kScaleBase + (uint32_t)(p & (kScaleSlots - 1)) * kScaleSlotBytes + (uint32_t)wave * 256;
-        dma4(ae_base + (int64_t)p * 4, ae_off, slot);
-        if (HAS_BE) dma4(be_base + (int64_t)p * 4, be_off, slot + kBT * 4);
+    // First exponent byte of scale block blk: blocks are 16 groups wide; the last one is
+    // shifted back so that its 16-byte copy ends exactly at the end of the row.
+    auto scale_block_start = [&](int blk) { const int st = blk * 16; return st + 16 <= G ? st : G - 16; };
+    auto issue_scales = [&](int blk) {
+        const uint32_t slot = lds0 + kScaleBase + (uint32_t)(blk & 1) * kScaleSlotBytes + (uint32_t)wave * 64 * 16;
+        const int st = scale_block_start(blk);
+        dma16(ae_base + st, ae_off, slot);
+        if (HAS_BE) dma16(be_base + st, be_off, slot + kBT * 16);
     };
 
-    // ---- LDS -> register fragment plan
-    const int gi = (i32 >> 2) & 3;
-    const int rd_lo = i32 * kStageK + ((h ^ gi) << 4);
-    const int rd_hi = i32 * kStageK + (((2 + h) ^ gi) << 4);
-    auto read_frags = [&](Frags &f, int u) {
-        const uint8_t *sa = big_smem + (u & (kStages - 1)) * kStageBytes + wm * 128 * kStageK;
-        const uint8_t *sb = big_smem + (u & (kStages - 1)) * kStageBytes + kBT * kStageK + wn * 128 * kStageK;
+    // ---- LDS -> register fragment plan (substep s of a stage = chunks 4s .. 4s+3 of a row)
+    const int sw = (i32 >> 1) & 7;
+    auto read_frags = [&](Frags &f, int P, int s) {
+        const uint8_t *sa = big_smem + (P & 1) * kSlotBytes + (wm * 128 + i32) * kStageK;
+        const uint8_t *sb = big_smem + (P & 1) * kSlotBytes + kBT * kStageK + (wn * 128 + i32) * kStageK;
+        const int lo_off = ((4 * s + h) ^ sw) << 4, hi_off = ((4 * s + 2 + h) ^ sw) << 4;
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            uint4 lo = *reinterpret_cast<const uint4 *>(sa + i * 32 * kStageK + rd_lo);
-            uint4 hi = *reinterpret_cast<const uint4 *>(sa + i * 32 * kStageK + rd_hi);
+            uint4 lo = *reinterpret_cast<const uint4 *>(sa + i * 32 * kStageK + lo_off);
+            uint4 hi = *reinterpret_cast<const uint4 *>(sa + i * 32 * kStageK + hi_off);
             f.a[i] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
         }
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            uint4 lo = *reinterpret_cast<const uint4 *>(sb + j * 32 * kStageK + rd_lo);
-            uint4 hi = *reinterpret_cast<const uint4 *>(sb + j * 32 * kStageK + rd_hi);
+            uint4 lo = *reinterpret_cast<const uint4 *>(sb + j * 32 * kStageK + lo_off);
+            uint4 hi = *reinterpret_cast<const uint4 *>(sb + j * 32 * kStageK + hi_off);
             f.b[j] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
         }
     };
-    // scale registers of a stage pair: byte 0 / byte 2 = this lane's group in the first /
-    // second stage of the pair (lanes of the upper half shift their dword down by one byte)
-    auto read_scales = [&](int (&sa)[4], int (&sb)[4], int p) {
-        const uint8_t *base = big_smem + kScaleBase + (p & (kScaleSlots - 1)) * kScaleSlotBytes;
+    // scale registers of stage P: byte 0 / byte 2 = this lane's group in substep 0 / 1 (lanes
+    // of the upper half shift their dword down by one byte, see shift_scales)
+    auto read_scales = [&](int (&sa)[4], int (&sb)[4], int P) {
+        const int blk = P >> 2;
+        const int dw = (4 * P - scale_block_start(blk));          // byte offset of the stage's dword
+        const uint8_t *base = big_smem + kScaleBase + (blk & 1) * kScaleSlotBytes + dw;
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-            sa[i] = (int)(*reinterpret_cast<const uint32_t *>(base + (wm * 128 + i * 32 + i32) * 4) >> (8 * h));
+        for (int i = 0; i < 4; i++) sa[i] = (int)*reinterpret_cast<const uint32_t *>(base + (wm * 128 + i * 32 + i32) * 16);
 #pragma unroll
         for (int j = 0; j < 4; j++)
-            sb[j] = HAS_BE ? (int)(*reinterpret_cast<const uint32_t *>(base + kBT * 4 + (wn * 128 + j * 32 + i32) * 4) >> (8 * h))
+            sb[j] = HAS_BE ? (int)*reinterpret_cast<const uint32_t *>(base + kBT * 16 + (wn * 128 + j * 32 + i32) * 16)
                            : 0x7F7F7F7F;
+    };
+    auto shift_scales = [&](int (&dst_a)[4], int (&dst_b)[4], const int (&sa)[4], const int (&sb)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            dst_a[i] = (int)((uint32_t)sa[i] >> (8 * h));
+            dst_b[i] = (int)((uint32_t)sb[i] >> (8 * h));
+        }
     };
 
     v16f acc[4][4];
@@ -195,105 +209,130 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
-    const int T = (int)(K / kStageK);   // even and >= 8 (host checks K % 128 == 0, K >= 512)
+    const int T = (int)(K / kStageK);   // >= 4 (host checks K % 128 == 0, K >= 512)
 
-    // prologue: stages 0, 1, 2 and the scales of pairs 0, 1 in flight
+    // prologue: scale block 0, stages 0 and 1 in flight; wait for all but stage 1
     issue_scales(0);
     issue_stage(0);
     issue_stage(1);
-    issue_scales(1);
-    issue_stage(2);
-    wait_vmcnt<8 + NSC>();            // everything but pair 1's scales and stage 2 has landed
-    stage_barrier();
+    wait_vmcnt<16>();
+    wait_lds_and_barrier();
 
-    Frags fe, fo;                     // fragments of the even / odd stage
-    int sa_cur[4], sb_cur[4], sa_nxt[4], sb_nxt[4];
-    read_frags(fe, 0);
-    read_scales(sa_cur, sb_cur, 0);
+    Frags fe, fo;                     // fragments of substep 0 / substep 1
+    int sa_cur[4], sb_cur[4], sa_raw[4], sb_raw[4];
+    read_frags(fe, 0, 0);
+    read_scales(sa_raw, sb_raw, 0);
+    shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
 
-#define MOSS_MFMA_STAGE(F, OPSEL)                                                                           \
+#define MOSS_MFMA_SUBSTEP(F, OPSEL)                                                                         \
+    __builtin_amdgcn_sched_barrier(0);                                                                      \
     _Pragma("unroll") for (int i = 0; i < 4; i++) _Pragma("unroll") for (int j = 0; j < 4; j++)            \
         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(F.b[j], F.a[i], acc[i][j], 0, 0, OPSEL, \
-                                                                    sb_cur[j], OPSEL, sa_cur[i]);
+                                                                    sb_cur[j], OPSEL, sa_cur[i]);           \
+    __builtin_amdgcn_sched_barrier(0);
 
-    // steady state: iteration t issues stage t+3, reads the fragments of stage t+1 and
-    // multiplies stage t
-    int t = 0;
-    for (; t + 4 < T; t += 2) {
-        issue_stage(t + 3);
-        read_frags(fo, t + 1);
-        MOSS_MFMA_STAGE(fe, 0)
-        wait_vmcnt<8>();              // stage t+2 (and older) landed; stage t+3 may be in flight
-        stage_barrier();
+    // One stage.  The order inside a substep is pinned (scheduling barriers): first the LDS
+    // reads for the next substep, then the 16 matrix instructions of the current one, so that
+    // the reads complete under the matrix work.  NEXT: a stage P+1 exists; ISSUE: so does P+2.
+    auto stage = [&](int P, auto next_tag, auto issue_tag) {
+        constexpr bool NEXT = decltype(next_tag)::value, ISSUE = decltype(issue_tag)::value;
+        // substep 0: multiply K[0,64) of stage P while fetching the fragments of K[64,128)
+        read_frags(fo, P, 1);
+        MOSS_MFMA_SUBSTEP(fe, 0)
+        if constexpr (NEXT) {
+            wait_vmcnt<0>();          // this wave's part of stage P+1 (and its scales) has landed
+            wait_lds_and_barrier();   // ... and everyone is done reading stage P's slot
+            // substep 1: refill the slot with stage P+2, fetch the first fragments of stage P+1
+            if constexpr (ISSUE) {
+                if (((P + 2) & 3) == 0) issue_scales((P + 2) >> 2);
+                issue_stage(P + 2);
+            }
+            read_frags(fe, P + 1, 0);
+            read_scales(sa_raw, sb_raw, P + 1);
+        }
+        MOSS_MFMA_SUBSTEP(fo, 2)
+        if constexpr (NEXT) shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int P = 0;
+    for (; P + 2 < T; P++) stage(P, yes{}, yes{});
+    stage(P, yes{}, no{});
+    stage(P + 1, no{}, no{});
+#undef MOSS_MFMA_SUBSTEP
 
-        issue_scales((t + 4) >> 1);
-        issue_stage(t + 4);
-        read_frags(fe, t + 2);
-        read_scales(sa_nxt, sb_nxt, (t + 2) >> 1);
-        MOSS_MFMA_STAGE(fo, 2)
-        wait_vmcnt<8 + NSC>();        // stage t+3 landed
-        stage_barrier();
-#pragma unroll
-        for (int i = 0; i < 4; i++) { sa_cur[i] = sa_nxt[i]; sb_cur[i] = sb_nxt[i]; }
-    }
-    // t == T-4: last stage to issue is T-1
-    issue_stage(t + 3);
-    read_frags(fo, t + 1);
-    MOSS_MFMA_STAGE(fe, 0)
-    wait_vmcnt<8>();
-    stage_barrier();
-    read_frags(fe, t + 2);
-    read_scales(sa_nxt, sb_nxt, (t + 2) >> 1);
-    MOSS_MFMA_STAGE(fo, 2)
-    wait_vmcnt<0>();
-    stage_barrier();
-#pragma unroll
-    for (int i = 0; i < 4; i++) { sa_cur[i] = sa_nxt[i]; sb_cur[i] = sb_nxt[i]; }
-    // t == T-2: nothing left to issue
-    read_frags(fo, t + 3);
-    MOSS_MFMA_STAGE(fe, 0)
-    MOSS_MFMA_STAGE(fo, 2)
-#undef MOSS_MFMA_STAGE
-
-    // ---- epilogue: one multiply by s_a * s_b, then the store.  Accumulator register v of
-    // lane (i32, h) in fragment (i, j) is out[m, n] with m = .. + i32 and
-    // n = .. + 8 (v / 4) + 4 h + v % 4: four consecutive n per register quad.
+    // ---- epilogue.  Accumulator register v of lane (i32, h) in fragment (i, j) is out[m, n]
+    // with m = .. + 32 i + i32 and n = .. + 32 j + 8 (v / 4) + 4 h + v % 4.  Scale, convert, stage
+    // the wave's 128 x 128 block through its private LDS region and store whole row pieces.
     const float scale = (*a_s) * (*b_s);
-    const bool vec_ok = (ld_out % 4 == 0);
+    wait_lds_and_barrier();           // all fragment reads are done: LDS can be reused
+    uint8_t *stg = big_smem + wave * kEpiWaveBytes;
+    const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;
+    const bool vec_ok = (ld_out % 8 == 0);
+    if (!out_f32) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int64_t m = m0 + wm * 128 + i * 32 + i32;
-        if (m >= M) continue;
+        for (int i = 0; i < 4; i++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
+            for (int j = 0; j < 4; j++)
 #pragma unroll
-            for (int qd = 0; qd < 4; qd++) {
-                const int64_t n = n0 + wn * 128 + j * 32 + qd * 8 + 4 * h;
-                if (n >= N) continue;
-                const float r0 = acc[i][j][4 * qd] * scale, r1 = acc[i][j][4 * qd + 1] * scale;
-                const float r2 = acc[i][j][4 * qd + 2] * scale, r3 = acc[i][j][4 * qd + 3] * scale;
-                if (out_f32) {
-                    float *o = reinterpret_cast<float *>(out) + m * ld_out + n;
-                    if (vec_ok && n + 3 < N) {
-                        float4 v = make_float4(r0, r1, r2, r3);
-                        if (accumulate) {
-                            const float4 p = *reinterpret_cast<const float4 *>(o);
-                            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-                        }
-                        *reinterpret_cast<float4 *>(o) = v;
-                    } else {
-                        const float r[4] = {r0, r1, r2, r3};
-                        for (int e = 0; e < 4 && n + e < N; e++) o[e] = accumulate ? o[e] + r[e] : r[e];
+                for (int qd = 0; qd < 4; qd++) {
+                    const uint32_t lo = bf16_rne(acc[i][j][4 * qd] * scale) | (bf16_rne(acc[i][j][4 * qd + 1] * scale) << 16);
+                    const uint32_t hi = bf16_rne(acc[i][j][4 * qd + 2] * scale) | (bf16_rne(acc[i][j][4 * qd + 3] * scale) << 16);
+                    *reinterpret_cast<uint2 *>(stg + (i * 32 + i32) * kEpiRowBytes + (j * 32 + qd * 8 + 4 * h) * 2) = make_uint2(lo, hi);
+                }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        // 16 lanes cover one 256-byte row piece, a wave instruction covers 4 rows
+        uint16_t *o = reinterpret_cast<uint16_t *>(out);
+        const int rr = lane >> 4, cc = (lane & 15) * 8;
+#pragma unroll 4
+        for (int it = 0; it < 32; it++) {
+            const int row = it * 4 + rr;
+            const int64_t m = mw + row, n = nw + cc;
+            if (m >= M || n >= N) continue;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * kEpiRowBytes + cc * 2);
+            uint16_t *dst = o + m * ld_out + n;
+            if (vec_ok && n + 7 < N) {
+                *reinterpret_cast<uint4 *>(dst) = v;
+            } else {
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                for (int e = 0; e < 8 && n + e < N; e++) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+    } else {
+        // FP32 output: two passes of 64 columns (a 256-byte row piece is 64 floats)
+        float *o = reinterpret_cast<float *>(out);
+        const int rr = lane >> 4, cc = (lane & 15) * 4;
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            if (half) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int jj = 0; jj < 2; jj++)
+#pragma unroll
+                    for (int qd = 0; qd < 4; qd++) {
+                        const int j = half * 2 + jj;
+                        *reinterpret_cast<float4 *>(stg + (i * 32 + i32) * kEpiRowBytes + (jj * 32 + qd * 8 + 4 * h) * 4) =
+                            make_float4(acc[i][j][4 * qd] * scale, acc[i][j][4 * qd + 1] * scale,
+                                        acc[i][j][4 * qd + 2] * scale, acc[i][j][4 * qd + 3] * scale);
                     }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll 4
+            for (int it = 0; it < 32; it++) {
+                const int row = it * 4 + rr;
+                const int64_t m = mw + row, n = nw + half * 64 + cc;
+                if (m >= M || n >= N) continue;
+                float4 v = *reinterpret_cast<const float4 *>(stg + row * kEpiRowBytes + cc * 4);
+                float *dst = o + m * ld_out + n;
+                if (vec_ok && n + 3 < N) {
+                    if (accumulate) {
+                        const float4 p = *reinterpret_cast<const float4 *>(dst);
+                        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+                    }
+                    *reinterpret_cast<float4 *>(dst) = v;
                 } else {
-                    uint16_t *o = reinterpret_cast<uint16_t *>(out) + m * ld_out + n;
-                    if (vec_ok && n + 3 < N) {
-                        *reinterpret_cast<uint2 *>(o) = make_uint2(bf16_rne(r0) | (bf16_rne(r1) << 16),
-                                                                   bf16_rne(r2) | (bf16_rne(r3) << 16));
-                    } else {
-                        const float r[4] = {r0, r1, r2, r3};
-                        for (int e = 0; e < 4 && n + e < N; e++) o[e] = (uint16_t)bf16_rne(r[e]);
-                    }
+                    const float r[4] = {v.x, v.y, v.z, v.w};
+                    for (int e = 0; e < 4 && n + e < N; e++) dst[e] = accumulate ? dst[e] + r[e] : r[e];
                 }
             }
         }

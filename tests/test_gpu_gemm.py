@@ -50,7 +50,7 @@ def assert_close(got, ref, na, nb, bf16, tag):
 @pytest.mark.parametrize("shape", [(16, 16, 32), (1, 1, 32), (5, 3, 64), (128, 128, 128), (200, 136, 96),
                                    (257, 129, 416), (130, 260, 1024), (64, 512, 160),
                                    # >= 8 tiles of 256 x 256 with K % 128 == 0: the large-tile kernel
-                                   (520, 776, 640), (1024, 2048, 512), (2049, 257, 1152)])
+                                   (520, 776, 640), (1024, 2048, 512), (2049, 257, 1152), (512, 1024, 2176)])
 @pytest.mark.parametrize("exps", ["both", "a_only", "none"])
 def test_random_codes_all_tile_edges(oracle, shape, exps):
     M, N, K = shape
