@@ -13,9 +13,10 @@
 //    global->LDS loads that never touch registers.  A stage is multiplied in two substeps
 //    of K = 64; fragments are double buffered in registers, so the fragments of the next
 //    substep are read from LDS while the 16 matrix instructions of the current one run.
-//  * The loads of stage P+2 are issued at the start of substep 1 of stage P (their slot is
-//    free from then on) and have to land by the end of substep 0 of stage P+1: two
-//    substeps (2 x 1024 matrix-core cycles) of latency hiding with 64 KiB in flight.
+//  * The loads of stage P+2 are issued during substep 1 of stage P (their slot is free from
+//    then on), one copy after each matrix instruction, and have to land by the end of
+//    substep 0 of stage P+1: one to two substeps (1024 matrix-core cycles each) of latency
+//    hiding with 64 KiB in flight.
 //  * One barrier per stage, at the end of substep 0; before it every wave waits for its
 //    own outstanding loads (stage P+1) and LDS reads.
 //  * E8M0 scale bytes travel the same way in blocks of 16 bytes (16 groups = K 512) per
@@ -143,13 +144,15 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     const uint8_t *a_base = a_q + m0 * K, *b_base = b_q + n0 * K;
     const uint8_t *ae_base = a_e + m0 * G, *be_base = HAS_BE ? b_e + n0 * G : nullptr;
 
-    auto issue_stage = [&](int P) {   // P = stage index (wave-uniform)
+    // copy number idx (0..15) of stage P: 0..7 = 8-row pieces of a, 8..15 = of b
+    auto issue_piece = [&](int P, int idx) {
         const uint32_t slot = lds0 + (uint32_t)(P & 1) * kSlotBytes + (uint32_t)wave * 64 * kStageK;
-        const uint8_t *ab = a_base + (int64_t)P * kStageK, *bb = b_base + (int64_t)P * kStageK;
+        if (idx < 8) dma16(a_base + (int64_t)P * kStageK, a_off[idx], slot + idx * 8 * kStageK);
+        else dma16(b_base + (int64_t)P * kStageK, b_off[idx - 8], slot + kBT * kStageK + (idx - 8) * 8 * kStageK);
+    };
+    auto issue_stage = [&](int P) {   // P = stage index (wave-uniform)
 #pragma unroll
-        for (int s = 0; s < 8; s++) dma16(ab, a_off[s], slot + s * 8 * kStageK);
-#pragma unroll
-        for (int s = 0; s < 8; s++) dma16(bb, b_off[s], slot + kBT * kStageK + s * 8 * kStageK);
+        for (int idx = 0; idx < 16; idx++) issue_piece(P, idx);
     };
     // First exponent byte of scale block blk: blocks are 16 groups wide; the last one is
     // shifted back so that its 16-byte copy ends exactly at the end of the row.
@@ -242,15 +245,25 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         if constexpr (NEXT) {
             wait_vmcnt<0>();          // this wave's part of stage P+1 (and its scales) has landed
             wait_lds_and_barrier();   // ... and everyone is done reading stage P's slot
-            // substep 1: refill the slot with stage P+2, fetch the first fragments of stage P+1
+            // substep 1: fetch the first fragments of stage P+1 and refill the freed slot with
+            // stage P+2.  The 16 copies are spread between the 16 matrix instructions: issued in
+            // one burst they would block this wave's instruction stream (and with it the matrix
+            // pipe) until the texture path has taken them all.
             if constexpr (ISSUE) {
                 if (((P + 2) & 3) == 0) issue_scales((P + 2) >> 2);
-                issue_stage(P + 2);
             }
             read_frags(fe, P + 1, 0);
             read_scales(sa_raw, sb_raw, P + 1);
         }
-        MOSS_MFMA_SUBSTEP(fo, 2)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int idx = 0; idx < 16; idx++) {
+            const int i = idx >> 2, j = idx & 3;
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fo.b[j], fo.a[i], acc[i][j], 0, 0, 2, sb_cur[j], 2,
+                                                                        sa_cur[i]);
+            if constexpr (ISSUE) issue_piece(P + 2, idx);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if constexpr (NEXT) shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
     };
     using yes = std::integral_constant<bool, true>;
