@@ -56,8 +56,9 @@ class Workload:
             L["y"] = torch.empty((TOKENS, N), dtype=bf16, device=dev)
             L["dx"] = torch.empty((TOKENS, K), dtype=bf16, device=dev)
             L["dw"] = torch.empty((N, K), dtype=f32, device=dev)
-            L["ws_q"] = torch.empty(1 << 16, dtype=u8, device=dev)
-            L["ws_w"] = torch.empty(1 << 16, dtype=u8, device=dev)
+            lib = moss.load()
+            L["ws_q"] = torch.empty(max(16, lib.moss_quant_workspace_bytes(TOKENS, max(K, N), 3)), dtype=u8, device=dev)
+            L["ws_w"] = torch.empty(max(16, lib.moss_weight_workspace_bytes(N, K)), dtype=u8, device=dev)
             moss.weight_autoscale_init(L["w"], L["state"], wq=L["wq"], wq_t=L["wq_t"], workspace=L["ws_w"])
             L["s_w"] = L["state"][4:8].view(f32)
             self.layers.append(L)

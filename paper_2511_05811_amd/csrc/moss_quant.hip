@@ -1,7 +1,8 @@
 // Two-level microscaling quantizer for gfx950 (paper Sec. 3.1, Eq. 1-2).
 //
 // Pass 1 (k_amax_bf16) streams X once and leaves one partial |x| maximum per
-// workgroup in the workspace.  Pass 2 (k_quant_row / k_quant_col) folds the
+// workgroup in the workspace.  Pass 2 (k_quant_row for row groups alone, k_quant_tile for
+// column groups or both groupings from one fetch of X) folds the
 // partials into the global scale s = amax/448 and then, per group of 32 values,
 // derives the power-of-two local scale from integer / exact FP32 comparisons and
 // emits E4M3 codes of (x * 2^-e) * (1/s).  Magnitudes of finite BF16 values order
@@ -27,24 +28,38 @@ __device__ __forceinline__ uint32_t chunk_absmax(const uint4 &r)
     return m;
 }
 
+constexpr int kAmaxUnroll = 4;
+
 __global__ __launch_bounds__(kQuantThreads) void k_amax_bf16(const uint16_t *__restrict__ x, int64_t n_chunks,
                                                              int chunks_per_row, int64_t ld, int dense,
                                                              uint32_t *__restrict__ partial)
 {
     __shared__ uint32_t red[kQuantThreads / kWave];
     uint32_t m = 0;
-    const int64_t stride = (int64_t)gridDim.x * kQuantThreads;
-    for (int64_t id = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; id < n_chunks; id += stride) {
-        int64_t off;
-        if (dense) {
-            off = id * 8;
-        } else {
-            int64_t row = id / chunks_per_row;
-            off = row * ld + (id - row * chunks_per_row) * 8;
+    // kAmaxUnroll independent 16-byte loads per thread and trip keep enough bytes in flight
+    const int64_t stride = (int64_t)gridDim.x * kQuantThreads * kAmaxUnroll;
+    for (int64_t id0 = (int64_t)blockIdx.x * kQuantThreads * kAmaxUnroll + threadIdx.x; id0 < n_chunks; id0 += stride) {
+        uint4 r[kAmaxUnroll];
+#pragma unroll
+        for (int u = 0; u < kAmaxUnroll; u++) {
+            const int64_t id = id0 + (int64_t)u * kQuantThreads;
+            r[u] = make_uint4(0, 0, 0, 0);
+            if (id < n_chunks) {
+                int64_t off;
+                if (dense) {
+                    off = id * 8;
+                } else {
+                    int64_t row = id / chunks_per_row;
+                    off = row * ld + (id - row * chunks_per_row) * 8;
+                }
+                r[u] = *reinterpret_cast<const uint4 *>(x + off);
+            }
         }
-        uint4 r = *reinterpret_cast<const uint4 *>(x + off);
-        uint32_t c = chunk_absmax(r);
-        m = c > m ? c : m;
+#pragma unroll
+        for (int u = 0; u < kAmaxUnroll; u++) {
+            uint32_t c = chunk_absmax(r[u]);
+            m = c > m ? c : m;
+        }
     }
     m = wave_max_u32(m);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
@@ -177,65 +192,125 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
     }
 }
 
-// Column grouping (groups of 32 along the rows, outputs transposed).  One wave owns a
-// 128-column stripe; each lane owns two neighbouring columns, so a wave-wide 4-byte
-// load covers 256 contiguous bytes of one row and a whole group lives in one lane's
-// registers (no cross-lane reduction).  A lane walks kColGroups consecutive row groups
-// so that its 32-byte code stores fill complete 128-byte lines of the transposed output.
-constexpr int kColGroups = 4;
+// Column grouping (groups of 32 along the rows, outputs stored transposed), optionally fused
+// with the row grouping so that X is fetched once for both outputs.
+//
+// A workgroup owns a 128 x 128 tile.  Every global access is a full line: 16 lanes read the
+// 256 bytes of a tile row with 16-byte loads, the row-grouped codes leave as 128 bytes per row,
+// and the transposed codes are staged through LDS so that 8 lanes write the 128 bytes of one
+// output row (= 128 consecutive input rows of one column).  Column maxima are reduced through
+// LDS: 16 partial rows per 32-row group, then one thread per (group, column).
+constexpr int kTile = 128;
+constexpr int kTilePitch = kTile + 4;   // bytes per staged output row (bank spread, dword aligned)
 
-template <bool CEIL>
-__global__ __launch_bounds__(kWave) void k_quant_col(const uint16_t *__restrict__ x, int64_t rows, int64_t cols,
-                                                     int64_t ld, const uint32_t *__restrict__ partial, int n_partial,
-                                                     uint8_t *__restrict__ q, uint8_t *__restrict__ e,
-                                                     float *__restrict__ s_global, int write_scale)
+template <bool ROW, bool CEIL>
+__global__ __launch_bounds__(kQuantThreads) void k_quant_tile(const uint16_t *__restrict__ x, int64_t rows, int64_t cols,
+                                                              int64_t ld, const uint32_t *__restrict__ partial,
+                                                              int n_partial, uint8_t *__restrict__ q_row,
+                                                              uint8_t *__restrict__ e_row, uint8_t *__restrict__ q_col,
+                                                              uint8_t *__restrict__ e_col, float *__restrict__ s_global)
 {
-    __shared__ uint32_t red[1];
-    const GlobalScale g = fold_global_scale(partial, n_partial, red);
-    if (write_scale && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *s_global = g.s;
+    __shared__ uint32_t red[kQuantThreads / kWave];
+    __shared__ __attribute__((aligned(16))) uint16_t cmax[4][16][kTile];   // partial column maxima per 32-row group
+    __shared__ __attribute__((aligned(16))) uint8_t cexp[4][kTile];        // E8M0 byte per (group, column)
+    __shared__ __attribute__((aligned(16))) uint8_t tt[kTile][kTilePitch]; // transposed codes [column][row]
 
-    const int64_t c0 = (int64_t)blockIdx.x * 128 + 2 * threadIdx.x;
-    if (c0 >= cols) return;
-    const int64_t n_groups = rows / kGroup;
-    const int64_t g_begin = (int64_t)blockIdx.y * kColGroups;
-    for (int gi = 0; gi < kColGroups; gi++) {
-        const int64_t grp = g_begin + gi;
-        if (grp >= n_groups) break;
-        const uint16_t *src = x + grp * kGroup * ld + c0;
-        uint32_t v[kGroup];
+    const GlobalScale g = fold_global_scale(partial, n_partial, red);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *s_global = g.s;
+
+    const int tid = threadIdx.x, rl = tid >> 4, ch = tid & 15;   // row lane (16 rows per pass), 16-byte chunk
+    const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
+    const int64_t col = c0 + ch * 8;
+    const bool col_ok = col < cols;                              // cols % 32 == 0: uniform per quad
+    const int64_t n_rgroups = rows / kGroup, n_cgroups = cols / kGroup;
+
+    uint4 raw[8];
 #pragma unroll
-        for (int j = 0; j < kGroup; j++) v[j] = *reinterpret_cast<const uint32_t *>(src + j * ld);
-        uint32_t m0 = 0, m1 = 0;
+    for (int it = 0; it < 8; it++) {
+        const int64_t row = r0 + it * 16 + rl;
+        raw[it] = make_uint4(0, 0, 0, 0);
+        if (col_ok && row < rows) raw[it] = *reinterpret_cast<const uint4 *>(x + row * ld + col);
+    }
+
+    if (ROW) {
 #pragma unroll
-        for (int j = 0; j < kGroup; j++) {
-            uint32_t lo = v[j] & 0x7FFFu, hi = (v[j] >> 16) & 0x7FFFu;
-            m0 = lo > m0 ? lo : m0;
-            m1 = hi > m1 ? hi : m1;
+        for (int it = 0; it < 8; it++) {
+            const int64_t row = r0 + it * 16 + rl;
+            const uint32_t gmax = quad_max_u32(chunk_absmax(raw[it]));
+            const int ex = local_exponent<CEIL>(gmax, g);
+            const float p2 = pow2_neg(ex);
+            const uint32_t w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
+            uint32_t out[2];
+#pragma unroll
+            for (int hh = 0; hh < 2; hh++) {
+                float y0 = (bf16_bits_to_f32(w[2 * hh] & 0xFFFFu) * p2) * g.inv_s;
+                float y1 = (__uint_as_float(w[2 * hh] & 0xFFFF0000u) * p2) * g.inv_s;
+                float y2 = (bf16_bits_to_f32(w[2 * hh + 1] & 0xFFFFu) * p2) * g.inv_s;
+                float y3 = (__uint_as_float(w[2 * hh + 1] & 0xFFFF0000u) * p2) * g.inv_s;
+                out[hh] = cvt4_e4m3_sat(y0, y1, y2, y3);
+            }
+            if (col_ok && row < rows) {
+                *reinterpret_cast<uint2 *>(q_row + row * cols + col) = make_uint2(out[0], out[1]);
+                if ((tid & 3) == 0) e_row[row * n_cgroups + (col >> 5)] = (uint8_t)(ex + 127);
+            }
         }
-        const int ex0 = local_exponent<CEIL>(m0, g), ex1 = local_exponent<CEIL>(m1, g);
-        const float p0 = pow2_neg(ex0), p1 = pow2_neg(ex1);
-        uint32_t o0[8], o1[8];
+    }
+
+    // partial column maxima of this thread's 8 columns over its 2 rows of each 32-row group
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            float a0 = (bf16_bits_to_f32(v[4 * j] & 0xFFFFu) * p0) * g.inv_s;
-            float a1 = (bf16_bits_to_f32(v[4 * j + 1] & 0xFFFFu) * p0) * g.inv_s;
-            float a2 = (bf16_bits_to_f32(v[4 * j + 2] & 0xFFFFu) * p0) * g.inv_s;
-            float a3 = (bf16_bits_to_f32(v[4 * j + 3] & 0xFFFFu) * p0) * g.inv_s;
-            o0[j] = cvt4_e4m3_sat(a0, a1, a2, a3);
-            float b0 = (__uint_as_float(v[4 * j] & 0xFFFF0000u) * p1) * g.inv_s;
-            float b1 = (__uint_as_float(v[4 * j + 1] & 0xFFFF0000u) * p1) * g.inv_s;
-            float b2 = (__uint_as_float(v[4 * j + 2] & 0xFFFF0000u) * p1) * g.inv_s;
-            float b3 = (__uint_as_float(v[4 * j + 3] & 0xFFFF0000u) * p1) * g.inv_s;
-            o1[j] = cvt4_e4m3_sat(b0, b1, b2, b3);
+    for (int rg = 0; rg < 4; rg++) {
+        const uint32_t wa[4] = {raw[2 * rg].x, raw[2 * rg].y, raw[2 * rg].z, raw[2 * rg].w};
+        const uint32_t wb[4] = {raw[2 * rg + 1].x, raw[2 * rg + 1].y, raw[2 * rg + 1].z, raw[2 * rg + 1].w};
+        uint32_t pm[4];
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            const uint32_t alo = wa[d] & 0x7FFFu, ahi = wa[d] & 0x7FFF0000u;
+            const uint32_t blo = wb[d] & 0x7FFFu, bhi = wb[d] & 0x7FFF0000u;
+            pm[d] = (alo > blo ? alo : blo) | (ahi > bhi ? ahi : bhi);
         }
-        uint8_t *d0 = q + c0 * rows + grp * kGroup;
-        uint8_t *d1 = d0 + rows;
-        reinterpret_cast<uint4 *>(d0)[0] = make_uint4(o0[0], o0[1], o0[2], o0[3]);
-        reinterpret_cast<uint4 *>(d0)[1] = make_uint4(o0[4], o0[5], o0[6], o0[7]);
-        reinterpret_cast<uint4 *>(d1)[0] = make_uint4(o1[0], o1[1], o1[2], o1[3]);
-        reinterpret_cast<uint4 *>(d1)[1] = make_uint4(o1[4], o1[5], o1[6], o1[7]);
-        e[c0 * n_groups + grp] = (uint8_t)(ex0 + 127);
-        e[(c0 + 1) * n_groups + grp] = (uint8_t)(ex1 + 127);
+        *reinterpret_cast<uint4 *>(&cmax[rg][rl][ch * 8]) = make_uint4(pm[0], pm[1], pm[2], pm[3]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+        const int idx = tid + k * kQuantThreads, rg = idx >> 7, c = idx & (kTile - 1);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 16; j++) {
+            const uint32_t v = cmax[rg][j][c];
+            m = v > m ? v : m;
+        }
+        const int ex = local_exponent<CEIL>(m, g);
+        cexp[rg][c] = (uint8_t)(ex + 127);
+        if (c0 + c < cols && r0 + rg * kGroup < rows) e_col[(c0 + c) * n_rgroups + (r0 >> 5) + rg] = (uint8_t)(ex + 127);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 8; it++) {
+        const uint2 eb = *reinterpret_cast<const uint2 *>(&cexp[it >> 1][ch * 8]);
+        const uint32_t w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
+        const int rr = it * 16 + rl;
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            const uint32_t ebytes = d < 2 ? eb.x : eb.y;
+            const int e0 = (int)((ebytes >> (16 * (d & 1))) & 0xFFu), e1 = (int)((ebytes >> (16 * (d & 1) + 8)) & 0xFFu);
+            // 2^-(e) with e = byte - 127: exponent field 254 - byte
+            const float p0 = __uint_as_float((uint32_t)(254 - e0) << 23), p1 = __uint_as_float((uint32_t)(254 - e1) << 23);
+            const float y0 = (bf16_bits_to_f32(w[d] & 0xFFFFu) * p0) * g.inv_s;
+            const float y1 = (__uint_as_float(w[d] & 0xFFFF0000u) * p1) * g.inv_s;
+            const uint32_t cc = cvt2_e4m3_sat(y0, y1);
+            tt[ch * 8 + 2 * d][rr] = (uint8_t)(cc & 0xFFu);
+            tt[ch * 8 + 2 * d + 1][rr] = (uint8_t)(cc >> 8);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int idx = tid + k * kQuantThreads, c = idx >> 3, piece = idx & 7;
+        if (c0 + c < cols && r0 + piece * 16 < rows) {
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(&tt[c][piece * 16]);
+            *reinterpret_cast<uint4 *>(q_col + (c0 + c) * rows + r0 + piece * 16) = make_uint4(src[0], src[1], src[2], src[3]);
+        }
     }
 }
 
@@ -274,13 +349,13 @@ extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t c
     const int64_t n_chunks = rows * chunks_per_row;
     const int dense = (ld == cols);
 
-    int64_t want_blocks = (n_chunks + kQuantThreads * 4 - 1) / (kQuantThreads * 4);
+    int64_t want_blocks = (n_chunks + kQuantThreads * kAmaxUnroll - 1) / (kQuantThreads * kAmaxUnroll);
     const int n_partial = (int)(want_blocks < kMaxPartials ? want_blocks : kMaxPartials);
     hipLaunchKernelGGL(k_amax_bf16, dim3(n_partial), dim3(kQuantThreads), 0, st, x, n_chunks, chunks_per_row, ld, dense,
                        partial);
     MOSS_LAUNCH_CHECK();
 
-    if (want_row) {
+    if (want_row && !want_col) {
         const int64_t per_block = (int64_t)kQuantThreads * kRowUnroll;
         const int64_t blocks = (n_chunks + per_block - 1) / per_block;
         if (blocks > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
@@ -293,16 +368,15 @@ extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t c
         MOSS_LAUNCH_CHECK();
     }
     if (want_col) {
-        const int64_t gx = (cols + 127) / 128;
-        const int64_t gy = (rows / kGroup + kColGroups - 1) / kColGroups;
-        if (gy > 65535) return MOSS_ERR_SHAPE;
-        const int write_scale = want_row ? 0 : 1;
-        if (ceil_mode)
-            hipLaunchKernelGGL(k_quant_col<true>, dim3((unsigned)gx, (unsigned)gy), dim3(kWave), 0, st, x, rows, cols, ld,
-                               partial, n_partial, q_col, e_col, s_global, write_scale);
-        else
-            hipLaunchKernelGGL(k_quant_col<false>, dim3((unsigned)gx, (unsigned)gy), dim3(kWave), 0, st, x, rows, cols, ld,
-                               partial, n_partial, q_col, e_col, s_global, write_scale);
+        const int64_t gx = (cols + kTile - 1) / kTile, gy = (rows + kTile - 1) / kTile;
+        if (gy > 65535 || gx > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
+        const dim3 grid((unsigned)gx, (unsigned)gy), block(kQuantThreads);
+#define MOSS_LAUNCH_TILE(R, C)                                                                                          \
+    hipLaunchKernelGGL((k_quant_tile<R, C>), grid, block, 0, st, x, rows, cols, ld, partial, n_partial, q_row, e_row, q_col, \
+                       e_col, s_global)
+        if (want_row) { if (ceil_mode) MOSS_LAUNCH_TILE(true, true); else MOSS_LAUNCH_TILE(true, false); }
+        else          { if (ceil_mode) MOSS_LAUNCH_TILE(false, true); else MOSS_LAUNCH_TILE(false, false); }
+#undef MOSS_LAUNCH_TILE
         MOSS_LAUNCH_CHECK();
     }
     return MOSS_OK;

@@ -14,21 +14,29 @@
 namespace moss {
 
 constexpr int kWThreads = 256;
-constexpr int kWMaxBlocks = 4096;
+constexpr int kWMaxBlocks = 4096;   // grid cap of the flat (1-D) kernels
+constexpr int kWTile = 128;         // tile edge of the 2-D kernel that also emits the transposed codes
 // |y| <= 464 rounds to 448 by itself (464 is the midpoint to the next grid point, tie to
 // even); beyond it the saturating cast changes the result: that is a clipped element.
 constexpr float kClip = 464.0f;
 
 struct WPartials {
-    float *amax;      // [kWMaxBlocks]
-    uint32_t *over;   // [kWMaxBlocks]
+    float *amax;      // [slots]
+    uint32_t *over;   // [slots]
 };
 
-__device__ __forceinline__ WPartials ws_partials(void *ws)
+// one slot per workgroup of the largest grid a call may launch
+__host__ __device__ inline int64_t partial_slots(int64_t rows, int64_t cols)
+{
+    const int64_t tiles = ((rows + kWTile - 1) / kWTile) * ((cols + kWTile - 1) / kWTile);
+    return tiles > kWMaxBlocks ? tiles : kWMaxBlocks;
+}
+
+__device__ __forceinline__ WPartials ws_partials(void *ws, int64_t slots)
 {
     WPartials p;
     p.amax = reinterpret_cast<float *>(ws);
-    p.over = reinterpret_cast<uint32_t *>(ws) + kWMaxBlocks;
+    p.over = reinterpret_cast<uint32_t *>(ws) + slots;
     return p;
 }
 
@@ -52,13 +60,14 @@ __device__ __forceinline__ void block_reduce(float &amax, uint32_t &over)
     }
 }
 
-__device__ __forceinline__ void block_reduce_store(float amax, uint32_t over, void *ws)
+__device__ __forceinline__ void block_reduce_store(float amax, uint32_t over, void *ws, int64_t slots)
 {
     block_reduce(amax, over);
     if (threadIdx.x == 0) {
-        WPartials p = ws_partials(ws);
-        p.amax[blockIdx.x] = amax;
-        p.over[blockIdx.x] = over;
+        WPartials p = ws_partials(ws, slots);
+        const int64_t b = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+        p.amax[b] = amax;
+        p.over[b] = over;
     }
 }
 
@@ -107,7 +116,7 @@ __global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w,
                                                           float *__restrict__ v, const void *__restrict__ g,
                                                           int64_t n4, AdamW a, double lr_term,
                                                           const moss_wscale_state *__restrict__ st,
-                                                          uint8_t *__restrict__ wq, void *ws)
+                                                          uint8_t *__restrict__ wq, void *ws, int64_t slots)
 {
     float inv_s = 0.0f;
     if (DO_CAST) {
@@ -136,11 +145,11 @@ __global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w,
             reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
         }
     }
-    block_reduce_store(amax, over, ws);
+    block_reduce_store(amax, over, ws, slots);
 }
 
 template <bool W_BF16>
-__global__ __launch_bounds__(kWThreads) void k_weight_amax(const void *__restrict__ w, int64_t n4, void *ws)
+__global__ __launch_bounds__(kWThreads) void k_weight_amax(const void *__restrict__ w, int64_t n4, void *ws, int64_t slots)
 {
     float amax = 0.0f;
     const int64_t stride = (int64_t)gridDim.x * kWThreads;
@@ -148,13 +157,13 @@ __global__ __launch_bounds__(kWThreads) void k_weight_amax(const void *__restric
         float4 wv = load_as_f32x4(w, i, W_BF16);
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
     }
-    block_reduce_store(amax, 0u, ws);
+    block_reduce_store(amax, 0u, ws, slots);
 }
 
 template <bool W_BF16>
 __global__ __launch_bounds__(kWThreads) void k_weight_cast(const void *__restrict__ w, int64_t n4,
                                                            const moss_wscale_state *__restrict__ st,
-                                                           uint8_t *__restrict__ wq, void *ws)
+                                                           uint8_t *__restrict__ wq, void *ws, int64_t slots)
 {
     const float s = scale_for_cast(st, 0, 0.0);
     const float inv_s = s > 0.0f ? 1.0f / s : 0.0f;
@@ -168,7 +177,75 @@ __global__ __launch_bounds__(kWThreads) void k_weight_cast(const void *__restric
         over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
         reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
     }
-    block_reduce_store(amax, over, ws);
+    block_reduce_store(amax, over, ws, slots);
+}
+
+// 2-D variant used when the transposed codes are wanted as well: a workgroup owns a
+// 128 x 128 tile, walks it 8 rows at a time (32 lanes x float4 = one 512-byte row piece),
+// writes the codes row-major (128 bytes per row) and collects them transposed in LDS;
+// at the end 8 lanes write the 128 bytes of each transposed row.  STEP: apply AdamW first
+// (fused optimizer step), otherwise cast only, with the scale already in the state.
+template <bool STEP, bool SRC_BF16>
+__global__ __launch_bounds__(kWThreads) void k_weight_tile(float *__restrict__ w, float *__restrict__ m,
+                                                           float *__restrict__ v, const void *__restrict__ src,
+                                                           int64_t rows, int64_t cols, AdamW a, double lr_term,
+                                                           const moss_wscale_state *__restrict__ st,
+                                                           uint8_t *__restrict__ wq, uint8_t *__restrict__ wq_t,
+                                                           void *ws, int64_t slots)
+{
+    constexpr int kPitch = kWTile + 4;
+    __shared__ __attribute__((aligned(16))) uint8_t tt[kWTile][kPitch];   // [column][row]
+    const float s = scale_for_cast(st, STEP ? 1 : 0, lr_term);
+    const float inv_s = s > 0.0f ? 1.0f / s : 0.0f;
+    const int tid = threadIdx.x, rl = tid >> 5, c4 = (tid & 31) * 4;
+    const int64_t r0 = (int64_t)blockIdx.y * kWTile, c0 = (int64_t)blockIdx.x * kWTile;
+    const int64_t col = c0 + c4;
+    float amax = 0.0f;
+    uint32_t over = 0;
+#pragma unroll 4
+    for (int it = 0; it < 16; it++) {
+        const int rr = it * 8 + rl;
+        const int64_t row = r0 + rr;
+        uint32_t code = 0;
+        if (row < rows && col < cols) {          // cols % 4 == 0: a float4 is inside or outside as a whole
+            const int64_t i4 = (row * cols + col) >> 2;
+            float4 wv;
+            if (STEP) {
+                wv = reinterpret_cast<float4 *>(w)[i4];
+                float4 mv = reinterpret_cast<float4 *>(m)[i4];
+                float4 vv = reinterpret_cast<float4 *>(v)[i4];
+                float4 gv = load_as_f32x4(src, i4, SRC_BF16);
+                adamw_elem(wv.x, mv.x, vv.x, gv.x, a);
+                adamw_elem(wv.y, mv.y, vv.y, gv.y, a);
+                adamw_elem(wv.z, mv.z, vv.z, gv.z, a);
+                adamw_elem(wv.w, mv.w, vv.w, gv.w, a);
+                reinterpret_cast<float4 *>(w)[i4] = wv;
+                reinterpret_cast<float4 *>(m)[i4] = mv;
+                reinterpret_cast<float4 *>(v)[i4] = vv;
+            } else {
+                wv = load_as_f32x4(src, i4, SRC_BF16);
+            }
+            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+            const float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
+            over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
+            code = cvt4_e4m3_sat(y0, y1, y2, y3);
+            reinterpret_cast<uint32_t *>(wq)[i4] = code;
+        }
+        tt[c4][rr] = (uint8_t)code;
+        tt[c4 + 1][rr] = (uint8_t)(code >> 8);
+        tt[c4 + 2][rr] = (uint8_t)(code >> 16);
+        tt[c4 + 3][rr] = (uint8_t)(code >> 24);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int idx = tid + k * kWThreads, c = idx >> 3, piece = idx & 7;
+        if (c0 + c < cols && r0 + piece * 16 < rows) {   // rows % 16 == 0: a 16-row piece is whole
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(&tt[c][piece * 16]);
+            *reinterpret_cast<uint4 *>(wq_t + (c0 + c) * rows + r0 + piece * 16) = make_uint4(p[0], p[1], p[2], p[3]);
+        }
+    }
+    block_reduce_store(amax, over, ws, slots);
 }
 
 enum FinalizeMode {
@@ -178,10 +255,10 @@ enum FinalizeMode {
     kFinCastOnly = 3  // after a cast-only pass: record amax, add overflow
 };
 
-__global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state *st, void *ws, int n_partial, int mode,
-                                                               double lr_term)
+__global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state *st, void *ws, int64_t slots,
+                                                               int n_partial, int mode, double lr_term)
 {
-    WPartials p = ws_partials(ws);
+    WPartials p = ws_partials(ws, slots);
     float amax = 0.0f;
     uint32_t over = 0;
     for (int i = threadIdx.x; i < n_partial; i += kWThreads) {
@@ -257,8 +334,8 @@ static int launch_transpose(const uint8_t *src, int64_t rows, int64_t cols, uint
 
 extern "C" size_t moss_weight_workspace_bytes(int64_t rows, int64_t cols)
 {
-    (void)rows; (void)cols;
-    return (size_t)moss::kWMaxBlocks * (sizeof(float) + sizeof(uint32_t));
+    if (rows <= 0 || cols <= 0) return 0;
+    return (size_t)moss::partial_slots(rows, cols) * (sizeof(float) + sizeof(uint32_t));
 }
 
 static int check_weight_common(int64_t rows, int64_t cols, const void *state, const void *wq, const void *wq_t,
@@ -267,11 +344,70 @@ static int check_weight_common(int64_t rows, int64_t cols, const void *state, co
     if (!state || !wq) return MOSS_ERR_NULL;
     if (rows <= 0 || cols <= 0 || (rows * cols) % 4) return MOSS_ERR_SHAPE;
     if (!moss_aligned16(wq) || ((uintptr_t)state & 7)) return MOSS_ERR_ALIGN;
-    (void)wq_t;
+    if (wq_t && !moss_aligned16(wq_t)) return MOSS_ERR_ALIGN;
     if (!ws || ws_bytes < moss_weight_workspace_bytes(rows, cols)) return MOSS_ERR_WORKSPACE;
     if (!moss_aligned16(ws)) return MOSS_ERR_ALIGN;
     return MOSS_OK;
 }
+
+namespace moss {
+
+// the 2-D kernel needs whole float4 per row and whole 16-row pieces per transposed row
+static bool tile_path_ok(int64_t rows, int64_t cols) { return cols % 4 == 0 && rows % 16 == 0; }
+
+struct WLaunch {
+    int64_t rows, cols, n4, slots;
+    int grid1d;
+    dim3 grid2d;
+    hipStream_t st;
+    void *ws;
+    moss_wscale_state *state;
+};
+
+static int finalize(const WLaunch &L, int n_partial, int mode, double lr_term)
+{
+    hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, L.st, L.state, L.ws, L.slots, n_partial, mode, lr_term);
+    MOSS_LAUNCH_CHECK();
+    return MOSS_OK;
+}
+
+// cast (and transposed copy) of the weights under the scale stored in the state
+static int cast_only(const WLaunch &L, const void *w, bool bf16, uint8_t *wq, uint8_t *wq_t)
+{
+    const AdamW none{};
+    if (wq_t && tile_path_ok(L.rows, L.cols)) {
+        if (bf16)
+            hipLaunchKernelGGL((k_weight_tile<false, true>), L.grid2d, dim3(kWThreads), 0, L.st, nullptr, nullptr, nullptr, w,
+                               L.rows, L.cols, none, 0.0, L.state, wq, wq_t, L.ws, L.slots);
+        else
+            hipLaunchKernelGGL((k_weight_tile<false, false>), L.grid2d, dim3(kWThreads), 0, L.st, nullptr, nullptr, nullptr, w,
+                               L.rows, L.cols, none, 0.0, L.state, wq, wq_t, L.ws, L.slots);
+        MOSS_LAUNCH_CHECK();
+        return finalize(L, (int)(L.grid2d.x * L.grid2d.y), kFinCastOnly, 0.0);
+    }
+    if (bf16)
+        hipLaunchKernelGGL(k_weight_cast<true>, dim3(L.grid1d), dim3(kWThreads), 0, L.st, w, L.n4, L.state, wq, L.ws, L.slots);
+    else
+        hipLaunchKernelGGL(k_weight_cast<false>, dim3(L.grid1d), dim3(kWThreads), 0, L.st, w, L.n4, L.state, wq, L.ws, L.slots);
+    MOSS_LAUNCH_CHECK();
+    int rc = finalize(L, L.grid1d, kFinCastOnly, 0.0);
+    if (rc) return rc;
+    if (wq_t) return launch_transpose(wq, L.rows, L.cols, wq_t, L.st);
+    return MOSS_OK;
+}
+
+static int make_launch(WLaunch &L, int64_t rows, int64_t cols, moss_wscale_state *state, void *ws, void *stream)
+{
+    L.rows = rows; L.cols = cols; L.n4 = rows * cols / 4; L.slots = partial_slots(rows, cols);
+    L.grid1d = grid_for(L.n4);
+    const int64_t gx = (cols + kWTile - 1) / kWTile, gy = (rows + kWTile - 1) / kWTile;
+    if (gy > 65535 || gx > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
+    L.grid2d = dim3((unsigned)gx, (unsigned)gy);
+    L.st = (hipStream_t)stream; L.ws = ws; L.state = state;
+    return MOSS_OK;
+}
+
+}  // namespace moss
 
 extern "C" int moss_weight_autoscale_init(const void *w, int w_dtype, int64_t rows, int64_t cols,
                                           moss_wscale_state *state, uint8_t *wq, uint8_t *wq_t,
@@ -283,25 +419,16 @@ extern "C" int moss_weight_autoscale_init(const void *w, int w_dtype, int64_t ro
     int rc = check_weight_common(rows, cols, state, wq, wq_t, workspace, workspace_bytes);
     if (rc) return rc;
     if (!moss_aligned16(w)) return MOSS_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)stream;
-    const int64_t n4 = rows * cols / 4;
-    const int grid = grid_for(n4);
-    if (w_dtype == MOSS_DT_BF16)
-        hipLaunchKernelGGL(k_weight_amax<true>, dim3(grid), dim3(kWThreads), 0, st, w, n4, workspace);
+    WLaunch L;
+    if ((rc = make_launch(L, rows, cols, state, workspace, stream))) return rc;
+    const bool bf16 = w_dtype == MOSS_DT_BF16;
+    if (bf16)
+        hipLaunchKernelGGL(k_weight_amax<true>, dim3(L.grid1d), dim3(kWThreads), 0, L.st, w, L.n4, workspace, L.slots);
     else
-        hipLaunchKernelGGL(k_weight_amax<false>, dim3(grid), dim3(kWThreads), 0, st, w, n4, workspace);
+        hipLaunchKernelGGL(k_weight_amax<false>, dim3(L.grid1d), dim3(kWThreads), 0, L.st, w, L.n4, workspace, L.slots);
     MOSS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinInit, 0.0);
-    MOSS_LAUNCH_CHECK();
-    if (w_dtype == MOSS_DT_BF16)
-        hipLaunchKernelGGL(k_weight_cast<true>, dim3(grid), dim3(kWThreads), 0, st, w, n4, state, wq, workspace);
-    else
-        hipLaunchKernelGGL(k_weight_cast<false>, dim3(grid), dim3(kWThreads), 0, st, w, n4, state, wq, workspace);
-    MOSS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinCastOnly, 0.0);
-    MOSS_LAUNCH_CHECK();
-    if (wq_t) return launch_transpose(wq, rows, cols, wq_t, st);
-    return MOSS_OK;
+    if ((rc = finalize(L, L.grid1d, kFinInit, 0.0))) return rc;
+    return cast_only(L, w, bf16, wq, wq_t);
 }
 
 extern "C" int moss_weight_autoscale_cast(float *w, float *m, float *v, const void *g, int g_dtype,
@@ -318,40 +445,39 @@ extern "C" int moss_weight_autoscale_cast(float *w, float *m, float *v, const vo
     if (g_dtype == MOSS_DT_F32 && !moss_aligned16(g)) return MOSS_ERR_ALIGN;
     if (args->step < 1) return MOSS_ERR_SHAPE;
 
-    hipStream_t st = (hipStream_t)stream;
-    const int64_t n4 = rows * cols / 4;
-    const int grid = grid_for(n4);
+    WLaunch L;
+    if ((rc = make_launch(L, rows, cols, state, workspace, stream))) return rc;
     AdamW a{args->lr, args->beta1, args->beta2, args->eps, args->weight_decay,
             args->one_minus_beta1, args->one_minus_beta2, args->bias_corr1, args->bias_corr2};
     const double lr_term = (double)args->margin * (double)args->lr;
     const bool rebase = args->interval > 0 && (args->step % args->interval) == 0;
     const bool gb = g_dtype == MOSS_DT_BF16;
+    const dim3 g1(L.grid1d), blk(kWThreads);
 
-    if (!rebase) {
+    if (rebase) {
+        // AdamW alone (it yields amax(W_new)), re-base the scale from it, then cast with the new scale
         if (gb)
-            hipLaunchKernelGGL((k_adamw_cast<true, true>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
-                               state, wq, workspace);
+            hipLaunchKernelGGL((k_adamw_cast<true, false>), g1, blk, 0, L.st, w, m, v, g, L.n4, a, lr_term, state, wq, workspace, L.slots);
         else
-            hipLaunchKernelGGL((k_adamw_cast<false, true>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
-                               state, wq, workspace);
+            hipLaunchKernelGGL((k_adamw_cast<false, false>), g1, blk, 0, L.st, w, m, v, g, L.n4, a, lr_term, state, wq, workspace, L.slots);
         MOSS_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinStep, lr_term);
-        MOSS_LAUNCH_CHECK();
-    } else {
-        if (gb)
-            hipLaunchKernelGGL((k_adamw_cast<true, false>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
-                               state, wq, workspace);
-        else
-            hipLaunchKernelGGL((k_adamw_cast<false, false>), dim3(grid), dim3(kWThreads), 0, st, w, m, v, g, n4, a, lr_term,
-                               state, wq, workspace);
-        MOSS_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinRebase, lr_term);
-        MOSS_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_weight_cast<false>, dim3(grid), dim3(kWThreads), 0, st, (const void *)w, n4, state, wq, workspace);
-        MOSS_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, st, state, workspace, grid, (int)kFinCastOnly, 0.0);
-        MOSS_LAUNCH_CHECK();
+        if ((rc = finalize(L, L.grid1d, kFinRebase, lr_term))) return rc;
+        return cast_only(L, w, false, wq, wq_t);
     }
-    if (wq_t) return launch_transpose(wq, rows, cols, wq_t, st);
+    if (wq_t && tile_path_ok(rows, cols)) {
+        if (gb)
+            hipLaunchKernelGGL((k_weight_tile<true, true>), L.grid2d, blk, 0, L.st, w, m, v, g, rows, cols, a, lr_term, state, wq, wq_t, workspace, L.slots);
+        else
+            hipLaunchKernelGGL((k_weight_tile<true, false>), L.grid2d, blk, 0, L.st, w, m, v, g, rows, cols, a, lr_term, state, wq, wq_t, workspace, L.slots);
+        MOSS_LAUNCH_CHECK();
+        return finalize(L, (int)(L.grid2d.x * L.grid2d.y), kFinStep, lr_term);
+    }
+    if (gb)
+        hipLaunchKernelGGL((k_adamw_cast<true, true>), g1, blk, 0, L.st, w, m, v, g, L.n4, a, lr_term, state, wq, workspace, L.slots);
+    else
+        hipLaunchKernelGGL((k_adamw_cast<false, true>), g1, blk, 0, L.st, w, m, v, g, L.n4, a, lr_term, state, wq, workspace, L.slots);
+    MOSS_LAUNCH_CHECK();
+    if ((rc = finalize(L, L.grid1d, kFinStep, lr_term))) return rc;
+    if (wq_t) return launch_transpose(wq, rows, cols, wq_t, L.st);
     return MOSS_OK;
 }
