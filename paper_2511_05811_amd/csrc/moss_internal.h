@@ -36,6 +36,43 @@ constexpr float kE4M3Max = 448.0f;  // Delta_max of E4M3 (paper Sec. 3.1)
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
+// Streaming ("nontemporal") global accesses for data that is touched once per kernel: they
+// do not allocate in the last-level cache, so a stream does not have to evict the dirty
+// lines earlier kernels left there.  Measured on a cold 64-256 MB read: 5.1-6.5 TB/s against
+// 2.7-3.0 TB/s with ordinary loads.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 ld_stream16(const void *p)
+{
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint2 ld_stream8(const void *p)
+{
+    const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+    return make_uint2(t.x, t.y);
+}
+__device__ __forceinline__ float4 ld_stream_f4(const void *p)
+{
+    const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void st_stream16(void *p, uint4 v)
+{
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+}
+__device__ __forceinline__ void st_stream8(void *p, uint2 v)
+{
+    __builtin_nontemporal_store(u32x2{v.x, v.y}, reinterpret_cast<u32x2 *>(p));
+}
+__device__ __forceinline__ void st_stream4(void *p, uint32_t v) { __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(p)); }
+__device__ __forceinline__ void st_stream_f4(void *p, float4 v)
+{
+    __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4 *>(p));
+}
+
 // Two FP32 values -> two E4M3 bytes in the low half of the result.  The hardware
 // converter rounds to nearest even; values are clamped to +-448 first so that the
 // cast saturates instead of producing the NaN code.

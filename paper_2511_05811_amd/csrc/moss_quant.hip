@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kQuantThreads) void k_amax_bf16(const uint16_t *__r
                     int64_t row = id / chunks_per_row;
                     off = row * ld + (id - row * chunks_per_row) * 8;
                 }
-                r[u] = *reinterpret_cast<const uint4 *>(x + off);
+                r[u] = ld_stream16(x + off);
             }
         }
 #pragma unroll
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
                 int64_t row = id / chunks_per_row;
                 off = row * ld + (id - row * chunks_per_row) * 8;
             }
-            raw[u] = *reinterpret_cast<const uint4 *>(x + off);
+            raw[u] = ld_stream16(x + off);
         }
     }
 #pragma unroll
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
             out[h] = cvt4_e4m3_sat(y0, y1, y2, y3);
         }
         if (id < n_chunks) {
-            *reinterpret_cast<uint2 *>(q + id * 8) = make_uint2(out[0], out[1]);
+            st_stream8(q + id * 8, make_uint2(out[0], out[1]));
             if ((threadIdx.x & 3) == 0) e[id >> 2] = (uint8_t)(ex + 127);
         }
     }
@@ -195,13 +195,24 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
 // Column grouping (groups of 32 along the rows, outputs stored transposed), optionally fused
 // with the row grouping so that X is fetched once for both outputs.
 //
-// A workgroup owns a 128 x 128 tile.  Every global access is a full line: 16 lanes read the
-// 256 bytes of a tile row with 16-byte loads, the row-grouped codes leave as 128 bytes per row,
-// and the transposed codes are staged through LDS so that 8 lanes write the 128 bytes of one
-// output row (= 128 consecutive input rows of one column).  Column maxima are reduced through
-// LDS: 16 partial rows per 32-row group, then one thread per (group, column).
+// A workgroup owns a 128 x 128 tile, one wave per 32-row group.  Lane (rl = lane / 16,
+// ch = lane % 16) holds rows 8 rl .. 8 rl + 7 of the group and the 8 columns of chunk ch, so
+//  * every global load is 16 bytes per lane and a wave instruction fetches four full
+//    256-byte row pieces;
+//  * a column group lives in the four lanes {ch, ch+16, ch+32, ch+48}: its maximum is a packed
+//    in-register maximum over 8 rows and two cross-lane steps -- no LDS, no barrier;
+//  * a row group (32 columns of one row) lives in a quad of lanes, as in k_quant_row;
+//  * a lane ends up with 8 consecutive rows of each of its columns = one 8-byte piece of a
+//    transposed output row; the pieces are collected in LDS and, after the only barrier,
+//    8 lanes write the 128 bytes of each transposed row.
 constexpr int kTile = 128;
-constexpr int kTilePitch = kTile + 4;   // bytes per staged output row (bank spread, dword aligned)
+constexpr int kTilePitch = kTile + 8;   // bytes per staged output row (8-byte aligned pieces, some bank spread)
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    const uint32_t alo = a & 0xFFFFu, blo = b & 0xFFFFu, ahi = a & 0xFFFF0000u, bhi = b & 0xFFFF0000u;
+    return (alo > blo ? alo : blo) | (ahi > bhi ? ahi : bhi);
+}
 
 template <bool ROW, bool CEIL>
 __global__ __launch_bounds__(kQuantThreads) void k_quant_tile(const uint16_t *__restrict__ x, int64_t rows, int64_t cols,
@@ -211,31 +222,29 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_tile(const uint16_t *__
                                                               uint8_t *__restrict__ e_col, float *__restrict__ s_global)
 {
     __shared__ uint32_t red[kQuantThreads / kWave];
-    __shared__ __attribute__((aligned(16))) uint16_t cmax[4][16][kTile];   // partial column maxima per 32-row group
-    __shared__ __attribute__((aligned(16))) uint8_t cexp[4][kTile];        // E8M0 byte per (group, column)
     __shared__ __attribute__((aligned(16))) uint8_t tt[kTile][kTilePitch]; // transposed codes [column][row]
 
     const GlobalScale g = fold_global_scale(partial, n_partial, red);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *s_global = g.s;
 
-    const int tid = threadIdx.x, rl = tid >> 4, ch = tid & 15;   // row lane (16 rows per pass), 16-byte chunk
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane >> 4, ch = lane & 15;
     const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
     const int64_t col = c0 + ch * 8;
-    const bool col_ok = col < cols;                              // cols % 32 == 0: uniform per quad
+    const int64_t rbase = r0 + wave * kGroup + rl * 8;           // first of this lane's 8 rows
+    const bool ok = col < cols && rbase < rows;                  // cols % 32 == 0, rows % 32 == 0: whole groups
     const int64_t n_rgroups = rows / kGroup, n_cgroups = cols / kGroup;
 
     uint4 raw[8];
 #pragma unroll
     for (int it = 0; it < 8; it++) {
-        const int64_t row = r0 + it * 16 + rl;
         raw[it] = make_uint4(0, 0, 0, 0);
-        if (col_ok && row < rows) raw[it] = *reinterpret_cast<const uint4 *>(x + row * ld + col);
+        if (ok) raw[it] = ld_stream16(x + (rbase + it) * ld + col);
     }
 
     if (ROW) {
 #pragma unroll
         for (int it = 0; it < 8; it++) {
-            const int64_t row = r0 + it * 16 + rl;
+            const int64_t row = rbase + it;
             const uint32_t gmax = quad_max_u32(chunk_absmax(raw[it]));
             const int ex = local_exponent<CEIL>(gmax, g);
             const float p2 = pow2_neg(ex);
@@ -249,67 +258,68 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_tile(const uint16_t *__
                 float y3 = (__uint_as_float(w[2 * hh + 1] & 0xFFFF0000u) * p2) * g.inv_s;
                 out[hh] = cvt4_e4m3_sat(y0, y1, y2, y3);
             }
-            if (col_ok && row < rows) {
-                *reinterpret_cast<uint2 *>(q_row + row * cols + col) = make_uint2(out[0], out[1]);
-                if ((tid & 3) == 0) e_row[row * n_cgroups + (col >> 5)] = (uint8_t)(ex + 127);
+            if (ok) {
+                st_stream8(q_row + row * cols + col, make_uint2(out[0], out[1]));
+                if ((lane & 3) == 0) e_row[row * n_cgroups + (col >> 5)] = (uint8_t)(ex + 127);
             }
         }
     }
 
-    // partial column maxima of this thread's 8 columns over its 2 rows of each 32-row group
-#pragma unroll
-    for (int rg = 0; rg < 4; rg++) {
-        const uint32_t wa[4] = {raw[2 * rg].x, raw[2 * rg].y, raw[2 * rg].z, raw[2 * rg].w};
-        const uint32_t wb[4] = {raw[2 * rg + 1].x, raw[2 * rg + 1].y, raw[2 * rg + 1].z, raw[2 * rg + 1].w};
-        uint32_t pm[4];
-#pragma unroll
-        for (int d = 0; d < 4; d++) {
-            const uint32_t alo = wa[d] & 0x7FFFu, ahi = wa[d] & 0x7FFF0000u;
-            const uint32_t blo = wb[d] & 0x7FFFu, bhi = wb[d] & 0x7FFF0000u;
-            pm[d] = (alo > blo ? alo : blo) | (ahi > bhi ? ahi : bhi);
-        }
-        *reinterpret_cast<uint4 *>(&cmax[rg][rl][ch * 8]) = make_uint4(pm[0], pm[1], pm[2], pm[3]);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 2; k++) {
-        const int idx = tid + k * kQuantThreads, rg = idx >> 7, c = idx & (kTile - 1);
-        uint32_t m = 0;
-#pragma unroll
-        for (int j = 0; j < 16; j++) {
-            const uint32_t v = cmax[rg][j][c];
-            m = v > m ? v : m;
-        }
-        const int ex = local_exponent<CEIL>(m, g);
-        cexp[rg][c] = (uint8_t)(ex + 127);
-        if (c0 + c < cols && r0 + rg * kGroup < rows) e_col[(c0 + c) * n_rgroups + (r0 >> 5) + rg] = (uint8_t)(ex + 127);
-    }
-    __syncthreads();
+    // column maxima: packed over this lane's 8 rows, then over the 4 row lanes of the wave
+    uint32_t pm[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int it = 0; it < 8; it++) {
-        const uint2 eb = *reinterpret_cast<const uint2 *>(&cexp[it >> 1][ch * 8]);
+        pm[0] = pk_max_u16(pm[0], raw[it].x & 0x7FFF7FFFu);
+        pm[1] = pk_max_u16(pm[1], raw[it].y & 0x7FFF7FFFu);
+        pm[2] = pk_max_u16(pm[2], raw[it].z & 0x7FFF7FFFu);
+        pm[3] = pk_max_u16(pm[3], raw[it].w & 0x7FFF7FFFu);
+    }
+#pragma unroll
+    for (int d = 0; d < 4; d++) {
+        pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 16, 64));
+        pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 32, 64));
+    }
+    // exponent and multiplier of each of the 8 columns
+    float p2c[8];
+    uint32_t ebytes[2] = {0, 0};
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        const uint32_t m = (pm[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+        const int ex = local_exponent<CEIL>(m, g);
+        p2c[j] = pow2_neg(ex);
+        ebytes[j >> 2] |= (uint32_t)(ex + 127) << (8 * (j & 3));
+    }
+    if (ok && rl == 0) {
+        const int64_t gidx = (r0 >> 5) + wave;
+#pragma unroll
+        for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(ebytes[j >> 2] >> (8 * (j & 3)));
+    }
+    // codes: for each column the 8 rows of this lane form one 8-byte piece of the transposed row
+    uint32_t pieces[8][2];
+#pragma unroll
+    for (int j = 0; j < 8; j++) pieces[j][0] = pieces[j][1] = 0;
+#pragma unroll
+    for (int it = 0; it < 8; it++) {
         const uint32_t w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
-        const int rr = it * 16 + rl;
 #pragma unroll
         for (int d = 0; d < 4; d++) {
-            const uint32_t ebytes = d < 2 ? eb.x : eb.y;
-            const int e0 = (int)((ebytes >> (16 * (d & 1))) & 0xFFu), e1 = (int)((ebytes >> (16 * (d & 1) + 8)) & 0xFFu);
-            // 2^-(e) with e = byte - 127: exponent field 254 - byte
-            const float p0 = __uint_as_float((uint32_t)(254 - e0) << 23), p1 = __uint_as_float((uint32_t)(254 - e1) << 23);
-            const float y0 = (bf16_bits_to_f32(w[d] & 0xFFFFu) * p0) * g.inv_s;
-            const float y1 = (__uint_as_float(w[d] & 0xFFFF0000u) * p1) * g.inv_s;
+            const float y0 = (bf16_bits_to_f32(w[d] & 0xFFFFu) * p2c[2 * d]) * g.inv_s;
+            const float y1 = (__uint_as_float(w[d] & 0xFFFF0000u) * p2c[2 * d + 1]) * g.inv_s;
             const uint32_t cc = cvt2_e4m3_sat(y0, y1);
-            tt[ch * 8 + 2 * d][rr] = (uint8_t)(cc & 0xFFu);
-            tt[ch * 8 + 2 * d + 1][rr] = (uint8_t)(cc >> 8);
+            pieces[2 * d][it >> 2] |= (cc & 0xFFu) << (8 * (it & 3));
+            pieces[2 * d + 1][it >> 2] |= (cc >> 8) << (8 * (it & 3));
         }
     }
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+        *reinterpret_cast<uint2 *>(&tt[ch * 8 + j][wave * kGroup + rl * 8]) = make_uint2(pieces[j][0], pieces[j][1]);
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 4; k++) {
         const int idx = tid + k * kQuantThreads, c = idx >> 3, piece = idx & 7;
         if (c0 + c < cols && r0 + piece * 16 < rows) {
             const uint32_t *src = reinterpret_cast<const uint32_t *>(&tt[c][piece * 16]);
-            *reinterpret_cast<uint4 *>(q_col + (c0 + c) * rows + r0 + piece * 16) = make_uint4(src[0], src[1], src[2], src[3]);
+            st_stream16(q_col + (c0 + c) * rows + r0 + piece * 16, make_uint4(src[0], src[1], src[2], src[3]));
         }
     }
 }

@@ -74,11 +74,11 @@ __device__ __forceinline__ void block_reduce_store(float amax, uint32_t over, vo
 __device__ __forceinline__ float4 load_as_f32x4(const void *p, int64_t i4, bool bf16)
 {
     if (bf16) {
-        uint2 r = reinterpret_cast<const uint2 *>(p)[i4];
+        uint2 r = ld_stream8(reinterpret_cast<const uint2 *>(p) + i4);
         return make_float4(bf16_bits_to_f32(r.x & 0xFFFFu), __uint_as_float(r.x & 0xFFFF0000u),
                            bf16_bits_to_f32(r.y & 0xFFFFu), __uint_as_float(r.y & 0xFFFF0000u));
     }
-    return reinterpret_cast<const float4 *>(p)[i4];
+    return ld_stream_f4(reinterpret_cast<const float4 *>(p) + i4);
 }
 
 struct AdamW {
@@ -127,22 +127,22 @@ __global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w,
     uint32_t over = 0;
     const int64_t stride = (int64_t)gridDim.x * kWThreads;
     for (int64_t i = (int64_t)blockIdx.x * kWThreads + threadIdx.x; i < n4; i += stride) {
-        float4 wv = reinterpret_cast<float4 *>(w)[i];
-        float4 mv = reinterpret_cast<float4 *>(m)[i];
-        float4 vv = reinterpret_cast<float4 *>(v)[i];
+        float4 wv = ld_stream_f4(reinterpret_cast<float4 *>(w) + i);
+        float4 mv = ld_stream_f4(reinterpret_cast<float4 *>(m) + i);
+        float4 vv = ld_stream_f4(reinterpret_cast<float4 *>(v) + i);
         float4 gv = load_as_f32x4(g, i, G_BF16);
         adamw_elem(wv.x, mv.x, vv.x, gv.x, a);
         adamw_elem(wv.y, mv.y, vv.y, gv.y, a);
         adamw_elem(wv.z, mv.z, vv.z, gv.z, a);
         adamw_elem(wv.w, mv.w, vv.w, gv.w, a);
-        reinterpret_cast<float4 *>(w)[i] = wv;
-        reinterpret_cast<float4 *>(m)[i] = mv;
-        reinterpret_cast<float4 *>(v)[i] = vv;
+        st_stream_f4(reinterpret_cast<float4 *>(w) + i, wv);
+        st_stream_f4(reinterpret_cast<float4 *>(m) + i, mv);
+        st_stream_f4(reinterpret_cast<float4 *>(v) + i, vv);
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
         if (DO_CAST) {
             float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
             over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
-            reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
+            st_stream4(reinterpret_cast<uint32_t *>(wq) + i, cvt4_e4m3_sat(y0, y1, y2, y3));
         }
     }
     block_reduce_store(amax, over, ws, slots);
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_cast(const void *__restric
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
         float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
         over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
-        reinterpret_cast<uint32_t *>(wq)[i] = cvt4_e4m3_sat(y0, y1, y2, y3);
+        st_stream4(reinterpret_cast<uint32_t *>(wq) + i, cvt4_e4m3_sat(y0, y1, y2, y3));
     }
     block_reduce_store(amax, over, ws, slots);
 }
@@ -211,17 +211,17 @@ __global__ __launch_bounds__(kWThreads) void k_weight_tile(float *__restrict__ w
             const int64_t i4 = (row * cols + col) >> 2;
             float4 wv;
             if (STEP) {
-                wv = reinterpret_cast<float4 *>(w)[i4];
-                float4 mv = reinterpret_cast<float4 *>(m)[i4];
-                float4 vv = reinterpret_cast<float4 *>(v)[i4];
+                wv = ld_stream_f4(reinterpret_cast<float4 *>(w) + i4);
+                float4 mv = ld_stream_f4(reinterpret_cast<float4 *>(m) + i4);
+                float4 vv = ld_stream_f4(reinterpret_cast<float4 *>(v) + i4);
                 float4 gv = load_as_f32x4(src, i4, SRC_BF16);
                 adamw_elem(wv.x, mv.x, vv.x, gv.x, a);
                 adamw_elem(wv.y, mv.y, vv.y, gv.y, a);
                 adamw_elem(wv.z, mv.z, vv.z, gv.z, a);
                 adamw_elem(wv.w, mv.w, vv.w, gv.w, a);
-                reinterpret_cast<float4 *>(w)[i4] = wv;
-                reinterpret_cast<float4 *>(m)[i4] = mv;
-                reinterpret_cast<float4 *>(v)[i4] = vv;
+                st_stream_f4(reinterpret_cast<float4 *>(w) + i4, wv);
+                st_stream_f4(reinterpret_cast<float4 *>(m) + i4, mv);
+                st_stream_f4(reinterpret_cast<float4 *>(v) + i4, vv);
             } else {
                 wv = load_as_f32x4(src, i4, SRC_BF16);
             }
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_tile(float *__restrict__ w
             const float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
             over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
             code = cvt4_e4m3_sat(y0, y1, y2, y3);
-            reinterpret_cast<uint32_t *>(wq)[i4] = code;
+            st_stream4(reinterpret_cast<uint32_t *>(wq) + i4, code);
         }
         tt[c4][rr] = (uint8_t)code;
         tt[c4 + 1][rr] = (uint8_t)(code >> 8);
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_tile(float *__restrict__ w
         const int idx = tid + k * kWThreads, c = idx >> 3, piece = idx & 7;
         if (c0 + c < cols && r0 + piece * 16 < rows) {   // rows % 16 == 0: a 16-row piece is whole
             const uint32_t *p = reinterpret_cast<const uint32_t *>(&tt[c][piece * 16]);
-            *reinterpret_cast<uint4 *>(wq_t + (c0 + c) * rows + r0 + piece * 16) = make_uint4(p[0], p[1], p[2], p[3]);
+            st_stream16(wq_t + (c0 + c) * rows + r0 + piece * 16, make_uint4(p[0], p[1], p[2], p[3]));
         }
     }
     block_reduce_store(amax, over, ws, slots);
