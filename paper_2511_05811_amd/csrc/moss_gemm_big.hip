@@ -11,8 +11,9 @@
 //    kernel needs 32 B/clk/CU at full matrix-core rate.)
 //  * Two LDS stage slots of 64 KiB (256 rows of a, 256 rows of b) filled by direct
 //    global->LDS loads that never touch registers.  A stage is multiplied in two substeps
-//    of K = 64; fragments are double buffered in registers, so the fragments of the next
-//    substep are read from LDS while the 16 matrix instructions of the current one run.
+//    of K = 64; fragments are double buffered in registers: the fragments of the next
+//    substep are read from LDS, one 16-byte read after each of the 16 matrix instructions
+//    of the current one.
 //  * The loads of stage P+2 are issued during substep 1 of stage P (their slot is free from
 //    then on), one copy after each matrix instruction, and have to land by the end of
 //    substep 0 of stage P+1: one to two substeps (1024 matrix-core cycles each) of latency
@@ -48,10 +49,8 @@ constexpr int kStageK = 128;                 // bytes of K per stage (one cache 
 constexpr int kSlotBytes = 2 * kBT * kStageK;          // a then b: 64 KiB
 constexpr int kScaleSlotBytes = 2 * kBT * 16;          // a then b, 16 exponent bytes (K 512) per row: 8 KiB
 constexpr int kScaleBase = 2 * kSlotBytes;             // 128 KiB
-constexpr int kBigLdsBytes = kScaleBase + 2 * kScaleSlotBytes;   // 144 KiB
-constexpr int kEpiRowBytes = 256 + 16;       // 128 BF16 (or 64 FP32) of one row + padding (keeps 16-byte alignment)
-constexpr int kEpiWaveBytes = 128 * kEpiRowBytes;      // 34 KiB per wave, 136 KiB in all
-static_assert(4 * kEpiWaveBytes <= kBigLdsBytes, "epilogue staging must fit");
+constexpr int kDummyBase = kScaleBase + 2 * kScaleSlotBytes;     // 144 KiB: 1 KiB per wave that nobody reads
+constexpr int kBigLdsBytes = kDummyBase + 4 * 1024;              // 148 KiB
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t big_smem[];
 
@@ -85,6 +84,32 @@ struct Frags {
     v8i a[4], b[4];
 };
 
+// The block-scaled matrix instruction as volatile inline assembly: volatile asm statements keep
+// their program order, which is what pins "one matrix instruction, one LDS read, one global->LDS
+// copy" in the main loop (compiler scheduling hints did not survive: all 16 matrix instructions
+// of a substep were emitted first and the memory instructions after them in one burst).
+// SEL = 0 / 2 picks scale byte 0 / 2 of both scale registers.  Independent accumulators back to
+// back need no wait states; the places where results are consumed add their own (see callers).
+template <int SEL>
+__device__ __forceinline__ void mfma_scaled(v16f &acc, const v8i &x, const v8i &y, int sx, int sy)
+{
+    if (SEL == 0)
+        asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel_hi:[0,0,0]"
+                     : "+a"(acc) : "v"(x), "v"(y), "v"(sx), "v"(sy));
+    else
+        asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel_hi:[1,1,0]"
+                     : "+a"(acc) : "v"(x), "v"(y), "v"(sx), "v"(sy));
+}
+__device__ __forceinline__ void pin() { asm volatile("" ::: "memory"); }
+
+// What a wave needs to know about one output tile: wave-uniform bases (scalar registers) and
+// its lanes' byte offsets for the global->LDS copies.
+struct TileCtx {
+    int64_t m0, n0;
+    const uint8_t *a_base, *b_base, *ae_base, *be_base;
+    uint32_t a_off[8], b_off[8], ae_off, be_off;
+};
+
 template <bool HAS_BE>
 __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, int64_t K,
                                                         const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_e,
@@ -99,96 +124,99 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)big_smem;
-
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
-    // contiguous range of tiles, walked in bands of 4 tile rows so that the 32 tiles an XCD
-    // works on at a time form a compact 4 x 8 block sharing a and b rows in that L2.
-    const int total = tiles_m * tiles_n;
-    int pid = blockIdx.x;
-    {
-        const int q = total >> 3, r = total & 7, xcd = pid & 7, idx = pid >> 3;
-        pid = (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + idx;
-    }
-    constexpr int GM = 4;
-    const int band = pid / (GM * tiles_n), rem = pid % (GM * tiles_n);
-    const int band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
-    // (the divisions run on the vector unit: tell the compiler the results are wave-uniform so
-    // that everything derived from them lives in scalar registers)
-    const int tm = __builtin_amdgcn_readfirstlane(band * GM + rem % band_rows);
-    const int tn = __builtin_amdgcn_readfirstlane(rem / band_rows);
-    const int64_t m0 = (int64_t)tm * kBT, n0 = (int64_t)tn * kBT;
-
-    // ---- global -> LDS copy plan: per stage a wave copies 64 rows of a and 64 rows of b in
-    // eight + eight wave-wide copies of 8 full rows (8 x 128 B = 1 KiB of LDS) each
     const int G = (int)(K >> 5);
-    uint32_t a_off[8], b_off[8];
-#pragma unroll
-    for (int s = 0; s < 8; s++) {
-        const int r = wave * 64 + s * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ ((r >> 1) & 7);
-        int64_t ra = m0 + r, rb = n0 + r;
-        ra = (ra < M ? ra : M - 1) - m0;
-        rb = (rb < N ? rb : N - 1) - n0;
-        a_off[s] = (uint32_t)(ra * K + c * 16);
-        b_off[s] = (uint32_t)(rb * K + c * 16);
-    }
-    uint32_t ae_off, be_off;   // scale copies: lane = row, 16 bytes of that row's exponent bytes
-    {
-        const int r = wave * 64 + lane;
-        int64_t ra = m0 + r, rb = n0 + r;
-        ra = (ra < M ? ra : M - 1) - m0;
-        rb = (rb < N ? rb : N - 1) - n0;
-        ae_off = (uint32_t)(ra * G);
-        be_off = (uint32_t)(rb * G);
-    }
-    const uint8_t *a_base = a_q + m0 * K, *b_base = b_q + n0 * K;
-    const uint8_t *ae_base = a_e + m0 * G, *be_base = HAS_BE ? b_e + n0 * G : nullptr;
+    const int T = (int)(K / kStageK);   // stages per tile, >= 4 (host checks K % 128 == 0, K >= 512)
+    const int NB = (T + 3) >> 2;        // scale blocks per tile
+    const int total = tiles_m * tiles_n;
+    const int n_my_tiles = (total - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
 
-    // copy number idx (0..15) of stage P: 0..7 = 8-row pieces of a, 8..15 = of b
-    auto issue_piece = [&](int P, int idx) {
-        const uint32_t slot = lds0 + (uint32_t)(P & 1) * kSlotBytes + (uint32_t)wave * 64 * kStageK;
-        if (idx < 8) dma16(a_base + (int64_t)P * kStageK, a_off[idx], slot + idx * 8 * kStageK);
-        else dma16(b_base + (int64_t)P * kStageK, b_off[idx - 8], slot + kBT * kStageK + (idx - 8) * 8 * kStageK);
-    };
-    auto issue_stage = [&](int P) {   // P = stage index (wave-uniform)
+    // The k-th tile of this (persistent) workgroup.  Workgroups are dealt round-robin to the 8
+    // XCDs (each with its own L2) and gridDim.x is a multiple of 8 whenever a workgroup has more
+    // than one tile, so tile number blockIdx.x + k gridDim.x stays on this XCD.  Every XCD gets a
+    // contiguous range of tiles, walked in bands of 4 tile rows: the 32 tiles an XCD works on at a
+    // time form a compact 4 x 8 block sharing a and b rows in that L2.
+    auto make_ctx = [&](int k, TileCtx &c) {
+        int pid = (int)blockIdx.x + k * (int)gridDim.x;
+        {
+            const int q = total >> 3, r = total & 7, xcd = pid & 7, idx = pid >> 3;
+            pid = (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + idx;
+        }
+        constexpr int GM = 4;
+        const int band = pid / (GM * tiles_n), rem = pid % (GM * tiles_n);
+        const int band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
+        // (the divisions run on the vector unit: tell the compiler the results are wave-uniform
+        // so that everything derived from them lives in scalar registers)
+        const int tm = __builtin_amdgcn_readfirstlane(band * GM + rem % band_rows);
+        const int tn = __builtin_amdgcn_readfirstlane(rem / band_rows);
+        c.m0 = (int64_t)tm * kBT;
+        c.n0 = (int64_t)tn * kBT;
+        // per stage a wave copies 64 rows of a and 64 rows of b in eight + eight wave-wide copies
+        // of 8 full rows (8 x 128 B = 1 KiB of LDS) each; rows beyond the matrix repeat the last row
 #pragma unroll
-        for (int idx = 0; idx < 16; idx++) issue_piece(P, idx);
+        for (int s = 0; s < 8; s++) {
+            const int r = wave * 64 + s * 8 + (lane >> 3);
+            const int ch = (lane & 7) ^ ((r >> 1) & 7);
+            int64_t ra = c.m0 + r, rb = c.n0 + r;
+            ra = (ra < M ? ra : M - 1) - c.m0;
+            rb = (rb < N ? rb : N - 1) - c.n0;
+            c.a_off[s] = (uint32_t)(ra * K + ch * 16);
+            c.b_off[s] = (uint32_t)(rb * K + ch * 16);
+        }
+        {   // scale copies: lane = row, 16 of that row's exponent bytes
+            const int r = wave * 64 + lane;
+            int64_t ra = c.m0 + r, rb = c.n0 + r;
+            ra = (ra < M ? ra : M - 1) - c.m0;
+            rb = (rb < N ? rb : N - 1) - c.n0;
+            c.ae_off = (uint32_t)(ra * G);
+            c.be_off = (uint32_t)(rb * G);
+        }
+        c.a_base = a_q + c.m0 * K;
+        c.b_base = b_q + c.n0 * K;
+        c.ae_base = a_e + c.m0 * G;
+        c.be_base = HAS_BE ? b_e + c.n0 * G : nullptr;
+    };
+
+    // copy number idx (0..15) of stage P of tile c into the stage slot `par`: 0..7 = 8-row pieces
+    // of a, 8..15 = of b
+    auto issue_piece = [&](const TileCtx &c, int P, int par, int idx, bool real = true) {
+        // real == false: the copy still runs (keeps the loop free of branches) but lands in a
+        // per-wave LDS area that nobody reads
+        const uint32_t slot = lds0 + (uint32_t)par * kSlotBytes + (uint32_t)wave * 64 * kStageK;
+        const uint32_t dummy = lds0 + kDummyBase + (uint32_t)wave * 1024;
+        if (idx < 8) dma16(c.a_base + (int64_t)P * kStageK, c.a_off[idx], real ? slot + idx * 8 * kStageK : dummy);
+        else dma16(c.b_base + (int64_t)P * kStageK, c.b_off[idx - 8], real ? slot + kBT * kStageK + (idx - 8) * 8 * kStageK : dummy);
+    };
+    auto issue_stage = [&](const TileCtx &c, int P, int par) {
+#pragma unroll
+        for (int idx = 0; idx < 16; idx++) issue_piece(c, P, par, idx);
     };
     // First exponent byte of scale block blk: blocks are 16 groups wide; the last one is
     // shifted back so that its 16-byte copy ends exactly at the end of the row.
     auto scale_block_start = [&](int blk) { const int st = blk * 16; return st + 16 <= G ? st : G - 16; };
-    auto issue_scales = [&](int blk) {
-        const uint32_t slot = lds0 + kScaleBase + (uint32_t)(blk & 1) * kScaleSlotBytes + (uint32_t)wave * 64 * 16;
+    auto issue_scales = [&](const TileCtx &c, int blk, int spar) {
+        const uint32_t slot = lds0 + kScaleBase + (uint32_t)spar * kScaleSlotBytes + (uint32_t)wave * 64 * 16;
         const int st = scale_block_start(blk);
-        dma16(ae_base + st, ae_off, slot);
-        if (HAS_BE) dma16(be_base + st, be_off, slot + kBT * 16);
+        dma16(c.ae_base + st, c.ae_off, slot);
+        if (HAS_BE) dma16(c.be_base + st, c.be_off, slot + kBT * 16);
     };
 
     // ---- LDS -> register fragment plan (substep s of a stage = chunks 4s .. 4s+3 of a row)
     const int sw = (i32 >> 1) & 7;
-    auto read_frags = [&](Frags &f, int P, int s) {
-        const uint8_t *sa = big_smem + (P & 1) * kSlotBytes + (wm * 128 + i32) * kStageK;
-        const uint8_t *sb = big_smem + (P & 1) * kSlotBytes + kBT * kStageK + (wn * 128 + i32) * kStageK;
-        const int lo_off = ((4 * s + h) ^ sw) << 4, hi_off = ((4 * s + 2 + h) ^ sw) << 4;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            uint4 lo = *reinterpret_cast<const uint4 *>(sa + i * 32 * kStageK + lo_off);
-            uint4 hi = *reinterpret_cast<const uint4 *>(sa + i * 32 * kStageK + hi_off);
-            f.a[i] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-        }
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            uint4 lo = *reinterpret_cast<const uint4 *>(sb + j * 32 * kStageK + lo_off);
-            uint4 hi = *reinterpret_cast<const uint4 *>(sb + j * 32 * kStageK + hi_off);
-            f.b[j] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-        }
+    // piece idx (0..15) of the fragments of substep s of the stage in slot `par`: fragment idx/2
+    // (0..3 = a, 4..7 = b), low or high four registers
+    auto read_piece = [&](Frags &f, int par, int s, int idx) {
+        const int fr = idx >> 1, half = idx & 1;
+        const uint8_t *base = big_smem + par * kSlotBytes +
+                              (fr < 4 ? (wm * 128 + fr * 32 + i32) * kStageK : kBT * kStageK + (wn * 128 + (fr - 4) * 32 + i32) * kStageK);
+        const uint4 v = *reinterpret_cast<const uint4 *>(base + (((4 * s + 2 * half + h) ^ sw) << 4));
+        v8i &dst = fr < 4 ? f.a[fr] : f.b[fr - 4];
+        dst[4 * half + 0] = (int)v.x; dst[4 * half + 1] = (int)v.y; dst[4 * half + 2] = (int)v.z; dst[4 * half + 3] = (int)v.w;
     };
-    // scale registers of stage P: byte 0 / byte 2 = this lane's group in substep 0 / 1 (lanes
-    // of the upper half shift their dword down by one byte, see shift_scales)
-    auto read_scales = [&](int (&sa)[4], int (&sb)[4], int P) {
+    // raw scale dwords of stage P (of a tile whose block 0 sits in scale slot parity sp0)
+    auto read_scales = [&](int (&sa)[4], int (&sb)[4], int P, int sp0) {
         const int blk = P >> 2;
-        const int dw = (4 * P - scale_block_start(blk));          // byte offset of the stage's dword
-        const uint8_t *base = big_smem + kScaleBase + (blk & 1) * kScaleSlotBytes + dw;
+        const int dw = 4 * P - scale_block_start(blk);            // byte offset of the stage's dword
+        const uint8_t *base = big_smem + kScaleBase + ((sp0 + blk) & 1) * kScaleSlotBytes + dw;
 #pragma unroll
         for (int i = 0; i < 4; i++) sa[i] = (int)*reinterpret_cast<const uint32_t *>(base + (wm * 128 + i * 32 + i32) * 16);
 #pragma unroll
@@ -196,6 +224,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
             sb[j] = HAS_BE ? (int)*reinterpret_cast<const uint32_t *>(base + kBT * 16 + (wn * 128 + j * 32 + i32) * 16)
                            : 0x7F7F7F7F;
     };
+    // byte 0 / byte 2 of a scale register = this lane's group in substep 0 / 1: lanes of the
+    // upper half shift their dword down by one byte
     auto shift_scales = [&](int (&dst_a)[4], int (&dst_b)[4], const int (&sa)[4], const int (&sb)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
@@ -205,151 +235,171 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     };
 
     v16f acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; i++)
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
-
-    const int T = (int)(K / kStageK);   // >= 4 (host checks K % 128 == 0, K >= 512)
-
-    // prologue: scale block 0, stages 0 and 1 in flight; wait for all but stage 1
-    issue_scales(0);
-    issue_stage(0);
-    issue_stage(1);
-    wait_vmcnt<16>();
-    wait_lds_and_barrier();
-
     Frags fe, fo;                     // fragments of substep 0 / substep 1
     int sa_cur[4], sb_cur[4], sa_raw[4], sb_raw[4];
-    read_frags(fe, 0, 0);
-    read_scales(sa_raw, sb_raw, 0);
-    shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
 
-#define MOSS_MFMA_SUBSTEP(F, OPSEL)                                                                         \
-    __builtin_amdgcn_sched_barrier(0);                                                                      \
-    _Pragma("unroll") for (int i = 0; i < 4; i++) _Pragma("unroll") for (int j = 0; j < 4; j++)            \
-        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(F.b[j], F.a[i], acc[i][j], 0, 0, OPSEL, \
-                                                                    sb_cur[j], OPSEL, sa_cur[i]);           \
-    __builtin_amdgcn_sched_barrier(0);
+    TileCtx cx;
+    make_ctx(0, cx);
+    // prologue: scale block 0, stages 0 and 1 of the first tile in flight
+    issue_scales(cx, 0, 0);
+    issue_stage(cx, 0, 0);
+    issue_stage(cx, 1, 1);
 
-    // One stage.  The order inside a substep is pinned (scheduling barriers): first the LDS
-    // reads for the next substep, then the 16 matrix instructions of the current one, so that
-    // the reads complete under the matrix work.  NEXT: a stage P+1 exists; ISSUE: so does P+2.
-    auto stage = [&](int P, auto next_tag, auto issue_tag) {
-        constexpr bool NEXT = decltype(next_tag)::value, ISSUE = decltype(issue_tag)::value;
-        // substep 0: multiply K[0,64) of stage P while fetching the fragments of K[64,128)
-        read_frags(fo, P, 1);
-        MOSS_MFMA_SUBSTEP(fe, 0)
-        if constexpr (NEXT) {
-            wait_vmcnt<0>();          // this wave's part of stage P+1 (and its scales) has landed
-            wait_lds_and_barrier();   // ... and everyone is done reading stage P's slot
-            // substep 1: fetch the first fragments of stage P+1 and refill the freed slot with
-            // stage P+2.  The 16 copies are spread between the 16 matrix instructions: issued in
-            // one burst they would block this wave's instruction stream (and with it the matrix
-            // pipe) until the texture path has taken them all.
-            if constexpr (ISSUE) {
-                if (((P + 2) & 3) == 0) issue_scales((P + 2) >> 2);
-            }
-            read_frags(fe, P + 1, 0);
-            read_scales(sa_raw, sb_raw, P + 1);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int idx = 0; idx < 16; idx++) {
-            const int i = idx >> 2, j = idx & 3;
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fo.b[j], fo.a[i], acc[i][j], 0, 0, 2, sb_cur[j], 2,
-                                                                        sa_cur[i]);
-            if constexpr (ISSUE) issue_piece(P + 2, idx);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (NEXT) shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
-    };
-    using yes = std::integral_constant<bool, true>;
-    using no = std::integral_constant<bool, false>;
-    int P = 0;
-    for (; P + 2 < T; P++) stage(P, yes{}, yes{});
-    stage(P, yes{}, no{});
-    stage(P + 1, no{}, no{});
-#undef MOSS_MFMA_SUBSTEP
-
-    // ---- epilogue.  Accumulator register v of lane (i32, h) in fragment (i, j) is out[m, n]
-    // with m = .. + 32 i + i32 and n = .. + 32 j + 8 (v / 4) + 4 h + v % 4.  Scale, convert, stage
-    // the wave's 128 x 128 block through its private LDS region and store whole row pieces.
     const float scale = (*a_s) * (*b_s);
-    wait_lds_and_barrier();           // all fragment reads are done: LDS can be reused
-    uint8_t *stg = big_smem + wave * kEpiWaveBytes;
-    const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;
     const bool vec_ok = (ld_out % 8 == 0);
-    if (!out_f32) {
+
+    for (int ti = 0; ti < n_my_tiles; ti++) {
+        const bool has_next = ti + 1 < n_my_tiles;
+        const int g0 = ti * T, sp0 = (ti * NB) & 1;      // global stage / scale block numbers of this tile's first
+        // Stage 0 and scale block 0 of this tile were issued two stages ago (or by the prologue),
+        // stage 1 just now: wait for all but the latter, then fetch the first fragments.
+        wait_vmcnt<16>();
+        wait_lds_and_barrier();
+#pragma unroll
+        for (int idx = 0; idx < 16; idx++) read_piece(fe, g0 & 1, 0, idx);
+        read_scales(sa_raw, sb_raw, 0, sp0);
+        shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
 #pragma unroll
         for (int i = 0; i < 4; i++)
 #pragma unroll
             for (int j = 0; j < 4; j++)
 #pragma unroll
-                for (int qd = 0; qd < 4; qd++) {
-                    const uint32_t lo = bf16_rne(acc[i][j][4 * qd] * scale) | (bf16_rne(acc[i][j][4 * qd + 1] * scale) << 16);
-                    const uint32_t hi = bf16_rne(acc[i][j][4 * qd + 2] * scale) | (bf16_rne(acc[i][j][4 * qd + 3] * scale) << 16);
-                    *reinterpret_cast<uint2 *>(stg + (i * 32 + i32) * kEpiRowBytes + (j * 32 + qd * 8 + 4 * h) * 2) = make_uint2(lo, hi);
-                }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        // 16 lanes cover one 256-byte row piece, a wave instruction covers 4 rows
-        uint16_t *o = reinterpret_cast<uint16_t *>(out);
-        const int rr = lane >> 4, cc = (lane & 15) * 8;
-#pragma unroll 4
-        for (int it = 0; it < 32; it++) {
-            const int row = it * 4 + rr;
-            const int64_t m = mw + row, n = nw + cc;
-            if (m >= M || n >= N) continue;
-            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * kEpiRowBytes + cc * 2);
-            uint16_t *dst = o + m * ld_out + n;
-            if (vec_ok && n + 7 < N) {
-                *reinterpret_cast<uint4 *>(dst) = v;
-            } else {
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-                for (int e = 0; e < 8 && n + e < N; e++) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+
+        // The stages of this tile.  There is exactly one copy of the 32 matrix instructions in the
+        // kernel (everything optional around them hangs on wave-uniform flags), so the 256
+        // accumulator registers never have to move.  The instruction order is pinned with scheduling
+        // barriers: each matrix instruction is followed by one 16-byte LDS read of the next substep's
+        // fragments and, in substep 1, by one global->LDS copy of the stage after next.  With one wave
+        // per SIMD a burst of memory instructions would block this wave's issue -- and so the matrix
+        // pipe -- until the LDS / texture queues had taken them all.
+        const int64_t m0 = cx.m0, n0 = cx.n0;
+        for (int P = 0; P < T; P++) {
+            const int par = (g0 + P) & 1;            // this stage's slot; the next stage sits in par ^ 1
+            const bool next = P + 1 < T;             // the epilogue, not this loop, hands over to the next tile
+            // what goes into slot `par` once it is free: stage P+2 of this tile, or stage 0 of the next
+            const bool own = P + 2 < T;
+            const bool issue = own || (P + 2 == T && has_next);
+            // (when there is nothing to issue -- the last stage, and the one before it for the last
+            // tile -- the copies are kept, aimed at stage T-1 again and at the unread LDS area)
+            const int iP = own ? P + 2 : (issue ? 0 : T - 1);
+            // substep 0: multiply K[0,64) while fetching the fragments of K[64,128)
+            asm volatile("s_nop 4" ::: "memory");    // scale registers were just written by vector ALU instructions
+#pragma unroll
+            for (int idx = 0; idx < 16; idx++) {
+                const int i = idx >> 2, j = idx & 3;
+                mfma_scaled<0>(acc[i][j], fe.b[j], fe.a[i], sb_cur[j], sa_cur[i]);
+                read_piece(fo, par, 1, idx);
+                pin();
             }
+            if (next) {
+                wait_vmcnt<0>();          // this wave's part of stage P+1 (and its scales) has landed
+                wait_lds_and_barrier();   // ... and everyone is done reading this stage's slot
+                read_scales(sa_raw, sb_raw, P + 1, sp0);
+            }
+            if (issue) {
+                if (!own) make_ctx(ti + 1, cx);      // from here on cx describes the next tile
+                if ((iP & 3) == 0) issue_scales(cx, iP >> 2, own ? (sp0 + (iP >> 2)) & 1 : (sp0 + NB) & 1);
+            }
+            // substep 1: multiply K[64,128), fetch the first fragments of stage P+1, refill the slot
+            pin();
+#pragma unroll
+            for (int idx = 0; idx < 16; idx++) {
+                const int i = idx >> 2, j = idx & 3;
+                mfma_scaled<2>(acc[i][j], fo.b[j], fo.a[i], sb_cur[j], sa_cur[i]);
+                read_piece(fe, par ^ 1, 0, idx);       // (after the last stage: read and never used)
+                issue_piece(cx, iP, par, idx, issue);
+            }
+            if (next) shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
         }
-    } else {
-        // FP32 output: two passes of 64 columns (a 256-byte row piece is 64 floats)
-        float *o = reinterpret_cast<float *>(out);
-        const int rr = lane >> 4, cc = (lane & 15) * 4;
+        // (stage 1 of the next tile belongs into the last stage's slot, which the epilogue uses first:
+        // it is issued after the epilogue)
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");   // let the last matrix instructions retire
+
+        // ---- epilogue.  Accumulator register v of lane (i32, h) in fragment (i, j) is out[m, n] with
+        // m = .. + 32 i + i32 and n = .. + 32 j + 8 (v / 4) + 4 h + v % 4.  Scale, convert, and stage
+        // 16 KiB at a time through the two 8 KiB pieces of the last stage's slot that this wave itself
+        // fills by copies (rows 64 wave .. of the a and of the b half), then store whole 256-byte row
+        // pieces.  Inside a 256-byte staged row the 16-byte chunk c sits at c ^ (row & 15).
+        wait_lds_and_barrier();   // every wave is done reading the last stage's fragments
+        const int epar = (g0 + T - 1) & 1;
+        uint8_t *pieceA = big_smem + epar * kSlotBytes + wave * 64 * kStageK;
+        uint8_t *pieceB = pieceA + kBT * kStageK;
+        const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;
+        if (!out_f32) {
+            uint16_t *o = reinterpret_cast<uint16_t *>(out);
 #pragma unroll
-        for (int half = 0; half < 2; half++) {
-            if (half) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            for (int rnd = 0; rnd < 2; rnd++) {
 #pragma unroll
-            for (int i = 0; i < 4; i++)
+                for (int ii = 0; ii < 2; ii++) {
+                    const int i = 2 * rnd + ii;
+                    uint8_t *pc = (ii ? pieceB : pieceA) + i32 * 256 + 8 * h;
 #pragma unroll
-                for (int jj = 0; jj < 2; jj++)
+                    for (int j = 0; j < 4; j++)
 #pragma unroll
-                    for (int qd = 0; qd < 4; qd++) {
-                        const int j = half * 2 + jj;
-                        *reinterpret_cast<float4 *>(stg + (i * 32 + i32) * kEpiRowBytes + (jj * 32 + qd * 8 + 4 * h) * 4) =
+                        for (int qd = 0; qd < 4; qd++) {
+                            const uint32_t lo = bf16_rne(acc[i][j][4 * qd] * scale) | (bf16_rne(acc[i][j][4 * qd + 1] * scale) << 16);
+                            const uint32_t hi = bf16_rne(acc[i][j][4 * qd + 2] * scale) | (bf16_rne(acc[i][j][4 * qd + 3] * scale) << 16);
+                            *reinterpret_cast<uint2 *>(pc + (((j * 4 + qd) ^ (i32 & 15)) << 4)) = make_uint2(lo, hi);
+                        }
+                }
+                // 16 lanes cover one 256-byte row piece (128 BF16), a wave instruction covers 4 rows
+                const int cc = lane & 15;
+#pragma unroll 4
+                for (int k = 0; k < 16; k++) {
+                    const int rl = 4 * k + (lane >> 4), ii = rl >> 5, rr = rl & 31;
+                    const uint4 v = *reinterpret_cast<const uint4 *>((ii ? pieceB : pieceA) + rr * 256 + ((cc ^ (rr & 15)) << 4));
+                    const int64_t m = mw + (2 * rnd + ii) * 32 + rr, n = nw + cc * 8;
+                    if (m >= M || n >= N) continue;
+                    uint16_t *dst = o + m * ld_out + n;
+                    if (vec_ok && n + 7 < N) {
+                        *reinterpret_cast<uint4 *>(dst) = v;
+                    } else {
+                        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                        for (int e = 0; e < 8 && n + e < N; e++) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged rows consumed before they are overwritten
+            }
+        } else {
+            float *o = reinterpret_cast<float *>(out);
+#pragma unroll
+            for (int i = 0; i < 4; i++) {       // one 32-row block per round: 32 rows x 512 B, halves in the two pieces
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+#pragma unroll
+                    for (int qd = 0; qd < 4; qd++)
+                        *reinterpret_cast<float4 *>(((j >> 1) ? pieceB : pieceA) + i32 * 256 +
+                                                    ((((j & 1) * 8 + qd * 2 + h) ^ (i32 & 15)) << 4)) =
                             make_float4(acc[i][j][4 * qd] * scale, acc[i][j][4 * qd + 1] * scale,
                                         acc[i][j][4 * qd + 2] * scale, acc[i][j][4 * qd + 3] * scale);
-                    }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                // 32 lanes cover one 512-byte row (128 floats), a wave instruction covers 2 rows
+                const int l32 = lane & 31, cc = l32 & 15;
 #pragma unroll 4
-            for (int it = 0; it < 32; it++) {
-                const int row = it * 4 + rr;
-                const int64_t m = mw + row, n = nw + half * 64 + cc;
-                if (m >= M || n >= N) continue;
-                float4 v = *reinterpret_cast<const float4 *>(stg + row * kEpiRowBytes + cc * 4);
-                float *dst = o + m * ld_out + n;
-                if (vec_ok && n + 3 < N) {
-                    if (accumulate) {
-                        const float4 p = *reinterpret_cast<const float4 *>(dst);
-                        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+                for (int k = 0; k < 16; k++) {
+                    const int rr = 2 * k + (lane >> 5);
+                    float4 v = *reinterpret_cast<const float4 *>(((l32 >> 4) ? pieceB : pieceA) + rr * 256 + ((cc ^ (rr & 15)) << 4));
+                    const int64_t m = mw + i * 32 + rr, n = nw + l32 * 4;
+                    if (m >= M || n >= N) continue;
+                    float *dst = o + m * ld_out + n;
+                    if (vec_ok && n + 3 < N) {
+                        if (accumulate) {
+                            const float4 p = *reinterpret_cast<const float4 *>(dst);
+                            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+                        }
+                        *reinterpret_cast<float4 *>(dst) = v;
+                    } else {
+                        const float r[4] = {v.x, v.y, v.z, v.w};
+                        for (int e = 0; e < 4 && n + e < N; e++) dst[e] = accumulate ? dst[e] + r[e] : r[e];
                     }
-                    *reinterpret_cast<float4 *>(dst) = v;
-                } else {
-                    const float r[4] = {v.x, v.y, v.z, v.w};
-                    for (int e = 0; e < 4 && n + e < N; e++) dst[e] = accumulate ? dst[e] + r[e] : r[e];
                 }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
         }
+        // the pieces are free again: fill them with this wave's part of stage 1 of the next tile
+        if (has_next) issue_stage(cx, 1, epar);
     }
+    wait_vmcnt<0>();   // no copy into LDS may be outstanding when the wave ends
 }
 
 }  // namespace moss
@@ -378,7 +428,12 @@ int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, 
         }
         attr_set[which] = true;
     }
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+    // persistent workgroups: one per compute unit (rounded down to a multiple of 8 so that the tiles
+    // of a workgroup stay on one XCD), or one per tile if there are fewer tiles
+    const int64_t total = tiles_m * tiles_n;
+    int cus = moss_internal_cu_count();
+    cus = cus >= 8 ? cus & ~7 : 8;
+    const dim3 grid((unsigned)(total < cus ? total : cus)), block(256);
     if (b_e)
         hipLaunchKernelGGL(k_gemm_mx_big<true>, grid, block, kBigLdsBytes, st, M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out,
                            out_f32, ld_out, accumulate, (int)tiles_m, (int)tiles_n);
