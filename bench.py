@@ -28,6 +28,9 @@ TOKENS = 8192
 LINEARS = [("qkv", 4096, 12288), ("o", 4096, 4096), ("gate", 4096, 11008), ("up", 4096, 11008), ("down", 11008, 4096)]
 QUANT_BYTES_PER_ELEM_BOTH = 4.0625   # read 2 B, write 2 x (1 + 1/32) B
 WEIGHT_BYTES_PER_ELEM = 30.0         # W, m, v read+write (24) + FP32 grad (4) + codes (1) + transposed codes (1)
+# Mean bytes per GEMM launch crossing the L2 boundary (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 from two
+# rocprofv3 --pmc runs of this script; summary and scale factors in profiles/bench_config3_hbm_traffic.md).
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 6.91e8
 
 
 def log(*a):
@@ -164,6 +167,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the measurement run one plain 256 MiB device copy (a kernel of known traffic "
+                         "against which hardware byte counters can be scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, 'How it would shard').")
@@ -238,7 +244,9 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "k_gemm (moss_gemm_fp8_mx)", "achieved": round(gemm_tflops, 2),
                      "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
                      "avg_launch_ms": round(gemm_ms / (cnt["gemm"] / args.steps), 4),
-                     "launches_per_step": cnt["gemm"] // args.steps, "traffic": None},
+                     "launches_per_step": cnt["gemm"] // args.steps, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                     "traffic_note": "bytes per launch leaving/entering the L2 (rocprofv3 FETCH_SIZE/WRITE_SIZE, scaled "
+                                     "against a plain copy); the operand re-fetches are served by the Infinity Cache"},
         "components": {
             "gemm_fp8": {"ms_per_step": round(gemm_ms, 4), "tflops": round(gemm_tflops, 2),
                          "frac_of_fp8_peak": round(gemm_tflops / PEAK_FP8_TFLOPS, 4)},
@@ -252,6 +260,12 @@ def main():
                                    "frac_of_bf16_peak": round(bf16_tflops / PEAK_BF16_TFLOPS, 4)},
         },
     }
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         try:
             result["cpu_baseline"] = cpu_baseline()
