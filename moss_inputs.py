@@ -121,6 +121,11 @@ def adversarial_activations(rows=64, cols=128, seed=7):
     out["signed_zeros"] = sgn
     tiny = base * np.float32(2.0 ** -120)
     out["tiny"] = tiny
+    tz = tiny.copy(); tz[:, 64:96] = 0.0; tz[7, :] = -0.0
+    out["tiny_zero_groups"] = tz
+    out["subnormal"] = base * np.float32(2.0 ** -127)      # BF16 subnormals, 1/s beyond FP32 range
+    mixed = base.copy(); mixed[:, 0:32] *= np.float32(2.0 ** -125); mixed[9, 40] = 200.0
+    out["tiny_groups_under_large_max"] = mixed
     big = base * np.float32(2.0 ** 90)
     out["big"] = big
     # group maxima placed on both sides of sqrt(2) * 2^k relative to the tensor maximum

@@ -20,6 +20,7 @@
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -146,6 +147,12 @@ int moss_oracle_quant_act_2level(const uint16_t *x, int64_t rows, int64_t cols, 
     float s = 1.0f;                       /* all-zero tensor: s = 1 */
     if (amax > 0.0) s = (float)amax / 448.0f;   /* one IEEE single division */
     float inv_s = 1.0f / s;               /* one IEEE single division */
+    /* Eq. 1 divides by a positive scale, so a zero input has code zero.  For a tensor whose
+     * maximum is below 448 * 2^-128 the single-precision reciprocal overflows and 0 * inf
+     * would be NaN: the largest finite single stands in for it (nonzero inputs still
+     * saturate or round as their true quotient would within a factor the format cannot
+     * resolve).                                                                            */
+    if (!isfinite(inv_s)) inv_s = FLT_MAX;
     *s_global = s;
 
     int64_t n_outer = axis == 0 ? rows : cols;        /* index of the output row */

@@ -14,18 +14,22 @@ namespace moss {
 constexpr int kQuantThreads = 256;
 constexpr int kMaxPartials = 2048;
 
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+// lane-wise maximum of two pairs of 16-bit unsigned values (one packed instruction)
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+
+constexpr uint32_t kMagMask = 0x7FFF7FFFu;   // the 15 magnitude bits of both BF16 halves of a word
+
 // max of the eight 15-bit magnitudes held in a 16-byte chunk
 __device__ __forceinline__ uint32_t chunk_absmax(const uint4 &r)
 {
-    uint32_t m = 0;
-    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
-        m = lo > m ? lo : m;
-        m = hi > m ? hi : m;
-    }
-    return m;
+    const uint32_t p = pk_max_u16(pk_max_u16(r.x & kMagMask, r.y & kMagMask), pk_max_u16(r.z & kMagMask, r.w & kMagMask));
+    const uint32_t lo = p & 0xFFFFu, hi = p >> 16;
+    return lo > hi ? lo : hi;
 }
 
 constexpr int kAmaxUnroll = 4;
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(kQuantThreads) void k_amax_bf16(const uint16_t *__r
 }
 
 struct GlobalScale {
-    float s, inv_s;   // s = amax/448 (1 for an all-zero tensor), inv_s = fl(1/s)
+    float s, inv_s;   // s = amax/448 (1 for an all-zero tensor), inv_s = fl(1/s), at most FLT_MAX
     float frac;       // amax = frac * 2^expo, frac in [0.5, 1)
     int expo;
     bool zero;
@@ -95,7 +99,7 @@ __device__ __forceinline__ GlobalScale fold_global_scale(const uint32_t *partial
     float amax = bf16_bits_to_f32(m);
     g.zero = (m == 0);
     g.s = g.zero ? 1.0f : amax / kE4M3Max;
-    g.inv_s = 1.0f / g.s;
+    g.inv_s = fminf(1.0f / g.s, __FLT_MAX__);   // finite, so that zero inputs keep code zero
     g.frac = __builtin_amdgcn_frexp_mantf(amax);
     g.expo = __builtin_amdgcn_frexp_expf(amax);
     return g;
@@ -127,12 +131,53 @@ __device__ __forceinline__ int local_exponent(uint32_t a_bits, const GlobalScale
 // 2^(-e) for e in [-127, 0] as an FP32 bit pattern
 __device__ __forceinline__ float pow2_neg(int e) { return __uint_as_float((uint32_t)(127 - e) << 23); }
 
+// The code of x in a group with exponent e is cast((x * 2^-e) * (1/s)) (Sec. 3.1, Eq. 1).  The
+// first product is exact, so x * (2^-e * (1/s)) rounds to the same value whenever that
+// single factor is finite; it is not for groups of tiny nonzero values under a small
+// global maximum, which take the two-product form.  An all-zero group (e = -127) gets the
+// factor 0: its codes are signed zeros either way.
+// group_factor returns that single factor, or NaN / infinity where the two-product form is needed.
+__device__ __forceinline__ float group_factor(uint32_t a_bits, int ex, const GlobalScale &g)
+{
+    return a_bits == 0 ? g.inv_s * 0.0f : pow2_neg(ex) * g.inv_s;
+}
+
+__device__ __forceinline__ bool factor_is_wide(float fused) { return !(fused < __builtin_inff()); }
+
+// 2^(-e) from the stored exponent byte e + 127
+__device__ __forceinline__ float pow2_neg_of_byte(uint32_t byte) { return __uint_as_float((254u - byte) << 23); }
+
+template <bool FUSED>
+__device__ __forceinline__ float scaled(float x, float fused, uint32_t ebyte, float inv_s)
+{
+    return FUSED ? x * fused : (x * pow2_neg_of_byte(ebyte)) * inv_s;
+}
+
+__device__ __forceinline__ float clamp448(float y) { return __builtin_amdgcn_fmed3f(y, kE4M3Max, -kE4M3Max); }
+
 __device__ __forceinline__ uint32_t quad_max_u32(uint32_t v)
 {
     uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
     v = o > v ? o : v;
     o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);           // quad_perm [2,3,0,1]
     return o > v ? o : v;
+}
+
+// E4M3 codes of the 8 values of a 16-byte chunk that share one group factor
+template <bool FUSED>
+__device__ __forceinline__ uint2 row_codes(const uint4 &r, float fused, uint32_t ebyte, float inv_s)
+{
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+    uint32_t out[2];
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const float y0 = scaled<FUSED>(bf16_bits_to_f32(w[2 * h] & 0xFFFFu), fused, ebyte, inv_s);
+        const float y1 = scaled<FUSED>(__uint_as_float(w[2 * h] & 0xFFFF0000u), fused, ebyte, inv_s);
+        const float y2 = scaled<FUSED>(bf16_bits_to_f32(w[2 * h + 1] & 0xFFFFu), fused, ebyte, inv_s);
+        const float y3 = scaled<FUSED>(__uint_as_float(w[2 * h + 1] & 0xFFFF0000u), fused, ebyte, inv_s);
+        out[h] = cvt4_e4m3_sat(y0, y1, y2, y3);
+    }
+    return make_uint2(out[0], out[1]);
 }
 
 // Row grouping: a group is 64 contiguous bytes = the 16-byte chunks of four
@@ -168,26 +213,26 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
             raw[u] = ld_stream16(x + off);
         }
     }
+    float f[kRowUnroll];
+    uint32_t eb[kRowUnroll];
+    bool wide = false;
 #pragma unroll
     for (int u = 0; u < kRowUnroll; u++) {
-        int64_t id = base + (int64_t)u * kQuantThreads;
         // the four lanes of a quad hold one group; n_chunks % 4 == 0 keeps quads uniform
-        uint32_t gmax = quad_max_u32(chunk_absmax(raw[u]));
-        int ex = local_exponent<CEIL>(gmax, g);
-        float p2 = pow2_neg(ex);
-        const uint32_t w[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
-        uint32_t out[2];
+        const uint32_t gmax = quad_max_u32(chunk_absmax(raw[u]));
+        const int ex = local_exponent<CEIL>(gmax, g);
+        eb[u] = (uint32_t)(ex + 127);
+        f[u] = group_factor(gmax, ex, g);
+        wide |= factor_is_wide(f[u]);
+    }
+    const bool any_wide = __any(wide);
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
-            float y0 = (bf16_bits_to_f32(w[2 * h] & 0xFFFFu) * p2) * g.inv_s;
-            float y1 = (__uint_as_float(w[2 * h] & 0xFFFF0000u) * p2) * g.inv_s;
-            float y2 = (bf16_bits_to_f32(w[2 * h + 1] & 0xFFFFu) * p2) * g.inv_s;
-            float y3 = (__uint_as_float(w[2 * h + 1] & 0xFFFF0000u) * p2) * g.inv_s;
-            out[h] = cvt4_e4m3_sat(y0, y1, y2, y3);
-        }
+    for (int u = 0; u < kRowUnroll; u++) {
+        const int64_t id = base + (int64_t)u * kQuantThreads;
+        const uint2 out = any_wide ? row_codes<false>(raw[u], f[u], eb[u], g.inv_s) : row_codes<true>(raw[u], f[u], eb[u], g.inv_s);
         if (id < n_chunks) {
-            st_stream8(q + id * 8, make_uint2(out[0], out[1]));
-            if ((threadIdx.x & 3) == 0) e[id >> 2] = (uint8_t)(ex + 127);
+            st_stream8(q + id * 8, out);
+            if ((threadIdx.x & 3) == 0) e[id >> 2] = (uint8_t)eb[u];
         }
     }
 }
@@ -208,18 +253,60 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
 constexpr int kTile = 128;
 constexpr int kTilePitch = kTile + 8;   // bytes per staged output row (8-byte aligned pieces, some bank spread)
 
-__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+// Codes of one lane's 8 x 8 values for both groupings.  Rows are taken two at a time: the
+// converter packs two values into two neighbouring bytes, so feeding it the same column
+// of two consecutive rows builds the transposed 8-row pieces without any byte shuffling.
+// rbytes / cbytes hold the 8 row-group and the 8 column-group exponent bytes.
+template <bool ROW, bool FUSED>
+__device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&rf)[8], const uint32_t (&rbytes)[2],
+                                           const float (&cf)[8], const uint32_t (&cbytes)[2], float inv_s, bool ok,
+                                           uint8_t *__restrict__ q_row_lane, int64_t cols, uint32_t (&pieces)[8][2])
 {
-    const uint32_t alo = a & 0xFFFFu, blo = b & 0xFFFFu, ahi = a & 0xFFFF0000u, bhi = b & 0xFFFF0000u;
-    return (alo > blo ? alo : blo) | (ahi > bhi ? ahi : bhi);
+#pragma unroll
+    for (int pr = 0; pr < 4; pr++) {
+        float x[2][8];
+#pragma unroll
+        for (int k = 0; k < 2; k++) {
+            const uint4 &r = raw[2 * pr + k];
+            const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+            for (int d = 0; d < 4; d++) {
+                x[k][2 * d] = bf16_bits_to_f32(w[d] & 0xFFFFu);
+                x[k][2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u);
+            }
+        }
+        if (ROW) {
+#pragma unroll
+            for (int k = 0; k < 2; k++) {
+                const int it = 2 * pr + k;
+                const uint32_t eb = (rbytes[it >> 2] >> (8 * (it & 3))) & 0xFFu;
+                float y[8];
+#pragma unroll
+                for (int j = 0; j < 8; j++) y[j] = scaled<FUSED>(x[k][j], rf[it], eb, inv_s);
+                const uint2 out = make_uint2(cvt4_e4m3_sat(y[0], y[1], y[2], y[3]), cvt4_e4m3_sat(y[4], y[5], y[6], y[7]));
+                if (ok) st_stream8(q_row_lane + it * cols, out);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const uint32_t eb = (cbytes[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+            const float a = clamp448(scaled<FUSED>(x[0][j], cf[j], eb, inv_s));
+            const float b = clamp448(scaled<FUSED>(x[1][j], cf[j], eb, inv_s));
+            uint32_t &word = pieces[j][pr >> 1];
+            if (pr & 1)
+                word = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)word, true);
+            else
+                word = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)word, false);
+        }
+    }
 }
 
 template <bool ROW, bool CEIL>
-__global__ __launch_bounds__(kQuantThreads) void k_quant_tile(const uint16_t *__restrict__ x, int64_t rows, int64_t cols,
-                                                              int64_t ld, const uint32_t *__restrict__ partial,
-                                                              int n_partial, uint8_t *__restrict__ q_row,
-                                                              uint8_t *__restrict__ e_row, uint8_t *__restrict__ q_col,
-                                                              uint8_t *__restrict__ e_col, float *__restrict__ s_global)
+__global__ __launch_bounds__(kQuantThreads, 4) void k_quant_tile(const uint16_t *__restrict__ x, int64_t rows, int64_t cols,
+                                                                 int64_t ld, const uint32_t *__restrict__ partial,
+                                                                 int n_partial, uint8_t *__restrict__ q_row,
+                                                                 uint8_t *__restrict__ e_row, uint8_t *__restrict__ q_col,
+                                                                 uint8_t *__restrict__ e_col, float *__restrict__ s_global)
 {
     __shared__ uint32_t red[kQuantThreads / kWave];
     __shared__ __attribute__((aligned(16))) uint8_t tt[kTile][kTilePitch]; // transposed codes [column][row]
@@ -241,75 +328,67 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_tile(const uint16_t *__
         if (ok) raw[it] = ld_stream16(x + (rbase + it) * ld + col);
     }
 
-    if (ROW) {
-#pragma unroll
-        for (int it = 0; it < 8; it++) {
-            const int64_t row = rbase + it;
-            const uint32_t gmax = quad_max_u32(chunk_absmax(raw[it]));
-            const int ex = local_exponent<CEIL>(gmax, g);
-            const float p2 = pow2_neg(ex);
-            const uint32_t w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
-            uint32_t out[2];
-#pragma unroll
-            for (int hh = 0; hh < 2; hh++) {
-                float y0 = (bf16_bits_to_f32(w[2 * hh] & 0xFFFFu) * p2) * g.inv_s;
-                float y1 = (__uint_as_float(w[2 * hh] & 0xFFFF0000u) * p2) * g.inv_s;
-                float y2 = (bf16_bits_to_f32(w[2 * hh + 1] & 0xFFFFu) * p2) * g.inv_s;
-                float y3 = (__uint_as_float(w[2 * hh + 1] & 0xFFFF0000u) * p2) * g.inv_s;
-                out[hh] = cvt4_e4m3_sat(y0, y1, y2, y3);
-            }
-            if (ok) {
-                st_stream8(q_row + row * cols + col, make_uint2(out[0], out[1]));
-                if ((lane & 3) == 0) e_row[row * n_cgroups + (col >> 5)] = (uint8_t)(ex + 127);
-            }
-        }
-    }
-
-    // column maxima: packed over this lane's 8 rows, then over the 4 row lanes of the wave
+    // group maxima: a row group (32 columns of one row) lives in a quad of lanes; a column
+    // group in this lane's 8 rows and those of the lanes 16, 32 and 48 further on
     uint32_t pm[4] = {0, 0, 0, 0};
+    float rf[8], cf[8];
+    uint32_t rbytes[2] = {0, 0}, cbytes[2] = {0, 0};
+    bool wide = false;
 #pragma unroll
     for (int it = 0; it < 8; it++) {
-        pm[0] = pk_max_u16(pm[0], raw[it].x & 0x7FFF7FFFu);
-        pm[1] = pk_max_u16(pm[1], raw[it].y & 0x7FFF7FFFu);
-        pm[2] = pk_max_u16(pm[2], raw[it].z & 0x7FFF7FFFu);
-        pm[3] = pk_max_u16(pm[3], raw[it].w & 0x7FFF7FFFu);
+        const uint32_t m0 = raw[it].x & kMagMask, m1 = raw[it].y & kMagMask, m2 = raw[it].z & kMagMask,
+                       m3 = raw[it].w & kMagMask;
+        pm[0] = pk_max_u16(pm[0], m0);
+        pm[1] = pk_max_u16(pm[1], m1);
+        pm[2] = pk_max_u16(pm[2], m2);
+        pm[3] = pk_max_u16(pm[3], m3);
+        if (ROW) {
+            const uint32_t p = pk_max_u16(pk_max_u16(m0, m1), pk_max_u16(m2, m3));
+            const uint32_t lo = p & 0xFFFFu, hi = p >> 16;
+            const uint32_t gmax = quad_max_u32(lo > hi ? lo : hi);
+            const int ex = local_exponent<CEIL>(gmax, g);
+            rf[it] = group_factor(gmax, ex, g);
+            wide |= factor_is_wide(rf[it]);
+            rbytes[it >> 2] |= (uint32_t)(ex + 127) << (8 * (it & 3));
+        }
     }
 #pragma unroll
     for (int d = 0; d < 4; d++) {
         pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 16, 64));
         pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 32, 64));
     }
-    // exponent and multiplier of each of the 8 columns
-    float p2c[8];
-    uint32_t ebytes[2] = {0, 0};
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         const uint32_t m = (pm[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
         const int ex = local_exponent<CEIL>(m, g);
-        p2c[j] = pow2_neg(ex);
-        ebytes[j >> 2] |= (uint32_t)(ex + 127) << (8 * (j & 3));
+        cf[j] = group_factor(m, ex, g);
+        wide |= factor_is_wide(cf[j]);
+        cbytes[j >> 2] |= (uint32_t)(ex + 127) << (8 * (j & 3));
     }
-    if (ok && rl == 0) {
-        const int64_t gidx = (r0 >> 5) + wave;
+
+    if (ok) {
+        if (ROW && (lane & 3) == 0) {
 #pragma unroll
-        for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(ebytes[j >> 2] >> (8 * (j & 3)));
+            for (int it = 0; it < 8; it++)
+                e_row[(rbase + it) * n_cgroups + (col >> 5)] = (uint8_t)(rbytes[it >> 2] >> (8 * (it & 3)));
+        }
+        if (rl == 0) {
+            const int64_t gidx = (r0 >> 5) + wave;
+#pragma unroll
+            for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
+        }
     }
-    // codes: for each column the 8 rows of this lane form one 8-byte piece of the transposed row
+
     uint32_t pieces[8][2];
 #pragma unroll
     for (int j = 0; j < 8; j++) pieces[j][0] = pieces[j][1] = 0;
-#pragma unroll
-    for (int it = 0; it < 8; it++) {
-        const uint32_t w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
-#pragma unroll
-        for (int d = 0; d < 4; d++) {
-            const float y0 = (bf16_bits_to_f32(w[d] & 0xFFFFu) * p2c[2 * d]) * g.inv_s;
-            const float y1 = (__uint_as_float(w[d] & 0xFFFF0000u) * p2c[2 * d + 1]) * g.inv_s;
-            const uint32_t cc = cvt2_e4m3_sat(y0, y1);
-            pieces[2 * d][it >> 2] |= (cc & 0xFFu) << (8 * (it & 3));
-            pieces[2 * d + 1][it >> 2] |= (cc >> 8) << (8 * (it & 3));
-        }
-    }
+    uint8_t *q_row_lane = ROW ? q_row + rbase * cols + col : nullptr;
+    if (__any(wide))
+        tile_codes<ROW, false>(raw, rf, rbytes, cf, cbytes, g.inv_s, ok, q_row_lane, cols, pieces);
+    else
+        tile_codes<ROW, true>(raw, rf, rbytes, cf, cbytes, g.inv_s, ok, q_row_lane, cols, pieces);
+
+    // the 8 rows of this lane form one 8-byte piece of each of its 8 transposed rows
 #pragma unroll
     for (int j = 0; j < 8; j++)
         *reinterpret_cast<uint2 *>(&tt[ch * 8 + j][wave * kGroup + rl * 8]) = make_uint2(pieces[j][0], pieces[j][1]);

@@ -58,8 +58,8 @@ def test_config1_activation(oracle):
         check_against_oracle(oracle, xb, flag, "config1 X")
 
 
-@pytest.mark.parametrize("name", ["zeros", "zero_groups", "one_outlier", "signed_zeros", "tiny", "big",
-                                  "sqrt2_boundary", "wide_range"])
+@pytest.mark.parametrize("name", ["zeros", "zero_groups", "one_outlier", "signed_zeros", "tiny", "tiny_zero_groups",
+                                  "subnormal", "tiny_groups_under_large_max", "big", "sqrt2_boundary", "wide_range"])
 def test_adversarial_tensors(oracle, name):
     xb = mi.adversarial_activations(64, 128)[name]
     for flag in (0, CEIL):
@@ -70,6 +70,12 @@ def test_adversarial_tensors(oracle, name):
 def test_ragged_shapes(oracle, shape):
     xb = mi.heavy_tailed_activation(shape[0], shape[1], seed=20 + shape[0])
     check_against_oracle(oracle, xb, 0, f"ragged {shape}")
+
+
+@pytest.mark.parametrize("shape,flag", [((4128, 2080), 0), ((4133, 2080), CEIL), ((1056, 8352), 0)])
+def test_many_tiles_with_ragged_edges(oracle, shape, flag):
+    xb = mi.heavy_tailed_activation(shape[0], shape[1], seed=40 + shape[1])
+    check_against_oracle(oracle, xb, flag, f"many tiles {shape}")
 
 
 def test_row_stride_larger_than_cols(oracle):

@@ -64,7 +64,10 @@ def brute_quant(xbits, axis, mode):
     outer, inner = x.shape
     amax = np.abs(x).max()
     s = np.float32(amax) / np.float32(448.0) if amax > 0 else np.float32(1.0)
-    inv_s = np.float32(1.0) / s
+    with np.errstate(over="ignore"):
+        inv_s = np.float32(1.0) / s
+    if not np.isfinite(inv_s):                     # reciprocal beyond FP32: largest finite value, zeros stay zero
+        inv_s = np.finfo(np.float32).max
     q = np.zeros((outer, inner), np.uint8)
     e = np.zeros((outer, inner // 32), np.uint8)
     for o in range(outer):
@@ -100,8 +103,8 @@ def test_bruteforce_rational_tiny(oracle, axis, mode):
     assert np.array_equal(q, qb)
 
 
-@pytest.mark.parametrize("name", ["zeros", "zero_groups", "one_outlier", "signed_zeros", "tiny", "big",
-                                  "sqrt2_boundary", "wide_range"])
+@pytest.mark.parametrize("name", ["zeros", "zero_groups", "one_outlier", "signed_zeros", "tiny", "tiny_zero_groups",
+                                  "subnormal", "tiny_groups_under_large_max", "big", "sqrt2_boundary", "wide_range"])
 def test_bruteforce_rational_adversarial(oracle, name):
     xb = mi.adversarial_activations(32, 64)[name]
     for axis in (0, 1):
