@@ -74,10 +74,13 @@ __device__ __forceinline__ void wait_lds_and_barrier()
     asm volatile("" ::: "memory");
 }
 
-__device__ __forceinline__ uint32_t bf16_rne(float f)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// two FP32 -> two BF16 (round to nearest even), a in the low half: one V_CVT_PK_BF16_F32
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 {
-    uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
 }
 
 struct Frags {
@@ -225,18 +228,23 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                            : 0x7F7F7F7F;
     };
     // byte 0 / byte 2 of a scale register = this lane's group in substep 0 / 1: lanes of the
-    // upper half shift their dword down by one byte
+    // upper half shift their dword down by one byte.  There is one register set per substep, and
+    // each is rewritten in the middle of the other substep, when the matrix instructions that
+    // read it have long retired and its next readers are eight instructions away: rewriting
+    // registers that matrix instructions in flight still name cost ~190 cycles per stage.  (The
+    // shifts are volatile asm so that they stay where they are put.)
+    const int sh8 = 8 * h;
     auto shift_scales = [&](int (&dst_a)[4], int (&dst_b)[4], const int (&sa)[4], const int (&sb)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            dst_a[i] = (int)((uint32_t)sa[i] >> (8 * h));
-            dst_b[i] = (int)((uint32_t)sb[i] >> (8 * h));
+            asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(dst_a[i]) : "v"(sh8), "v"(sa[i]));
+            asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(dst_b[i]) : "v"(sh8), "v"(sb[i]));
         }
     };
 
     v16f acc[4][4];
     Frags fe, fo;                     // fragments of substep 0 / substep 1
-    int sa_cur[4], sb_cur[4], sa_raw[4], sb_raw[4];
+    int sa0[4], sb0[4], sa1[4], sb1[4], sa_raw[4], sb_raw[4];   // scales of substep 0 / substep 1, raw dwords
 
     TileCtx cx;
     make_ctx(0, cx);
@@ -258,7 +266,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
 #pragma unroll
         for (int idx = 0; idx < 16; idx++) read_piece(fe, g0 & 1, 0, idx);
         read_scales(sa_raw, sb_raw, 0, sp0);
-        shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
+        shift_scales(sa0, sb0, sa_raw, sb_raw);
+        asm volatile("s_nop 4" ::: "memory");    // vector ALU write -> scale operand of a matrix instruction
 #pragma unroll
         for (int i = 0; i < 4; i++)
 #pragma unroll
@@ -284,12 +293,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
             // tile -- the copies are kept, aimed at stage T-1 again and at the unread LDS area)
             const int iP = own ? P + 2 : (issue ? 0 : T - 1);
             // substep 0: multiply K[0,64) while fetching the fragments of K[64,128)
-            asm volatile("s_nop 4" ::: "memory");    // scale registers were just written by vector ALU instructions
 #pragma unroll
             for (int idx = 0; idx < 16; idx++) {
                 const int i = idx >> 2, j = idx & 3;
-                mfma_scaled<0>(acc[i][j], fe.b[j], fe.a[i], sb_cur[j], sa_cur[i]);
+                mfma_scaled<0>(acc[i][j], fe.b[j], fe.a[i], sb0[j], sa0[i]);
                 read_piece(fo, par, 1, idx);
+                if (idx == 8) shift_scales(sa1, sb1, sa_raw, sb_raw);     // this stage's scales for substep 1
                 pin();
             }
             if (next) {
@@ -306,11 +315,11 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
 #pragma unroll
             for (int idx = 0; idx < 16; idx++) {
                 const int i = idx >> 2, j = idx & 3;
-                mfma_scaled<2>(acc[i][j], fo.b[j], fo.a[i], sb_cur[j], sa_cur[i]);
+                mfma_scaled<2>(acc[i][j], fo.b[j], fo.a[i], sb1[j], sa1[i]);
                 read_piece(fe, par ^ 1, 0, idx);       // (after the last stage: read and never used)
                 issue_piece(cx, iP, par, idx, issue);
+                if (idx == 8 && next) shift_scales(sa0, sb0, sa_raw, sb_raw);   // the next stage's, for its substep 0
             }
-            if (next) shift_scales(sa_cur, sb_cur, sa_raw, sb_raw);
         }
         // (stage 1 of the next tile belongs into the last stage's slot, which the epilogue uses first:
         // it is issued after the epilogue)
@@ -338,8 +347,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                     for (int j = 0; j < 4; j++)
 #pragma unroll
                         for (int qd = 0; qd < 4; qd++) {
-                            const uint32_t lo = bf16_rne(acc[i][j][4 * qd] * scale) | (bf16_rne(acc[i][j][4 * qd + 1] * scale) << 16);
-                            const uint32_t hi = bf16_rne(acc[i][j][4 * qd + 2] * scale) | (bf16_rne(acc[i][j][4 * qd + 3] * scale) << 16);
+                            const uint32_t lo = pack_bf16(acc[i][j][4 * qd] * scale, acc[i][j][4 * qd + 1] * scale);
+                            const uint32_t hi = pack_bf16(acc[i][j][4 * qd + 2] * scale, acc[i][j][4 * qd + 3] * scale);
                             *reinterpret_cast<uint2 *>(pc + (((j * 4 + qd) ^ (i32 & 15)) << 4)) = make_uint2(lo, hi);
                         }
                 }
