@@ -85,6 +85,15 @@ int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_
                           uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
                           float *s_global, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Mid-sized and large tensors are quantized by one launch whose workgroups meet once, through
+ * a few words of the workspace, to agree on the global maximum (Sec. 3.1: one FP32 scale per
+ * tensor).  A workgroup polls for the result at most `polls` times before it computes the
+ * maximum from X by itself, so the kernel ends even if its workgroups cannot all run at once;
+ * the outputs are the same on either path.  Process-wide, takes effect from the next call; the
+ * default is 32768.  0 makes every workgroup that finds the result not yet published take the
+ * slow path (used by the tests). */
+void moss_quant_set_poll_limit(unsigned polls);
+
 /* ---------------------------------------------------------------------------
  * Per-tensor FP8 weights with automatic scaling  (paper Sec. 3.2, Eq. 6 and the
  * interval re-scaling of its last paragraph; AdamW as in Sec. 2.2 Eq. 3; App. C).

@@ -58,6 +58,8 @@ def load():
     L.moss_quant_workspace_bytes.restype = sz
     L.moss_quant_workspace_bytes.argtypes = [i64, i64, u32]
     L.moss_quant_act_2level.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moss_quant_set_poll_limit.restype = None
+    L.moss_quant_set_poll_limit.argtypes = [u32]
     L.moss_weight_workspace_bytes.restype = sz
     L.moss_weight_workspace_bytes.argtypes = [i64, i64]
     L.moss_weight_autoscale_init.argtypes = [vp, ci, i64, i64, vp, vp, vp, vp, sz, vp]
@@ -124,6 +126,11 @@ def quant_act_2level(x, flags=MOSS_Q_ROW, out=None, workspace=None):
                                  _ptr(s), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "moss_quant_act_2level")
     return dict(q_row=q_row, e_row=e_row, q_col=q_col, e_col=e_col, s=s)
+
+
+def quant_set_poll_limit(polls):
+    """Bound of the one-launch quantizer's wait for the grid-wide maximum (0: slow path)."""
+    load().moss_quant_set_poll_limit(int(polls))
 
 
 def new_wscale_state(device):

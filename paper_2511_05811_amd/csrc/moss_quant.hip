@@ -7,6 +7,8 @@
 // derives the power-of-two local scale from integer / exact FP32 comparisons and
 // emits E4M3 codes of (x * 2^-e) * (1/s).  Magnitudes of finite BF16 values order
 // like their low 15 bits, so every maximum is an integer maximum and is exact.
+#include <atomic>
+
 #include "moss_internal.h"
 
 namespace moss {
@@ -81,6 +83,8 @@ struct GlobalScale {
     bool zero;
 };
 
+__device__ __forceinline__ GlobalScale make_global_scale(uint32_t amax_bits);
+
 // Every workgroup folds the (few) partial maxima itself: cheaper than another launch.
 __device__ __forceinline__ GlobalScale fold_global_scale(const uint32_t *partial, int n_partial, uint32_t *red)
 {
@@ -95,6 +99,11 @@ __device__ __forceinline__ GlobalScale fold_global_scale(const uint32_t *partial
     const int nw = blockDim.x >> 6;
     m = red[0];
     for (int i = 1; i < nw; i++) m = red[i] > m ? red[i] : m;
+    return make_global_scale(m);
+}
+
+__device__ __forceinline__ GlobalScale make_global_scale(uint32_t m)
+{
     GlobalScale g;
     float amax = bf16_bits_to_f32(m);
     g.zero = (m == 0);
@@ -257,9 +266,10 @@ constexpr int kTilePitch = kTile + 8;   // bytes per staged output row (8-byte a
 // converter packs two values into two neighbouring bytes, so feeding it the same column
 // of two consecutive rows builds the transposed 8-row pieces without any byte shuffling.
 // rbytes / cbytes hold the 8 row-group and the 8 column-group exponent bytes.
-template <bool ROW, bool FUSED>
+// n_ok = how many of this lane's 8 rows exist (row grouping alone allows any row count).
+template <bool ROW, bool COL, bool FUSED>
 __device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&rf)[8], const uint32_t (&rbytes)[2],
-                                           const float (&cf)[8], const uint32_t (&cbytes)[2], float inv_s, bool ok,
+                                           const float (&cf)[8], const uint32_t (&cbytes)[2], float inv_s, int n_ok,
                                            uint8_t *__restrict__ q_row_lane, int64_t cols, uint32_t (&pieces)[8][2])
 {
 #pragma unroll
@@ -284,9 +294,10 @@ __device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&
 #pragma unroll
                 for (int j = 0; j < 8; j++) y[j] = scaled<FUSED>(x[k][j], rf[it], eb, inv_s);
                 const uint2 out = make_uint2(cvt4_e4m3_sat(y[0], y[1], y[2], y[3]), cvt4_e4m3_sat(y[4], y[5], y[6], y[7]));
-                if (ok) st_stream8(q_row_lane + it * cols, out);
+                if (it < n_ok) st_stream8(q_row_lane + it * cols, out);
             }
         }
+        if (!COL) continue;
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const uint32_t eb = (cbytes[j >> 2] >> (8 * (j & 3))) & 0xFFu;
@@ -297,6 +308,167 @@ __device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&
                 word = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)word, true);
             else
                 word = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)word, false);
+        }
+    }
+}
+
+// The two-product form of tile_codes, out of line: it runs only for tiles that hold a group of
+// tiny nonzero values under a small global maximum, and inlining it next to the one-product
+// form doubled the code and the register pressure of every tile.  Its operands travel through
+// a struct in private memory that only the cold branch ever fills.
+struct WideTile {
+    uint4 raw[8];
+    float rf[8], cf[8];
+    uint32_t rbytes[2], cbytes[2];
+    float inv_s;
+    int n_ok;
+    uint8_t *q_row_lane;
+    int64_t cols;
+    uint32_t pieces[8][2];
+};
+
+template <bool ROW, bool COL>
+__device__ __attribute__((noinline)) void tile_codes_wide(WideTile *w)
+{
+    tile_codes<ROW, COL, false>(w->raw, w->rf, w->rbytes, w->cf, w->cbytes, w->inv_s, w->n_ok, w->q_row_lane, w->cols,
+                                w->pieces);
+}
+
+struct TileShape {
+    int64_t rows, cols, ld;
+};
+
+// This lane's 8 x 16 bytes of the tile whose first element is (r0, c0); zeros outside X.
+__device__ __forceinline__ void load_tile(uint4 (&raw)[8], const uint16_t *__restrict__ x, const TileShape &sh, int64_t r0,
+                                          int64_t c0)
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane >> 4, ch = lane & 15;
+    const int64_t col = c0 + ch * 8, rbase = r0 + wave * kGroup + rl * 8;
+    const bool ok = col < sh.cols;
+#pragma unroll
+    for (int it = 0; it < 8; it++) {
+        raw[it] = make_uint4(0, 0, 0, 0);
+        if (ok && rbase + it < sh.rows) raw[it] = ld_stream16(x + (rbase + it) * sh.ld + col);
+    }
+}
+
+// largest 15-bit magnitude among this lane's 64 values
+__device__ __forceinline__ uint32_t tile_absmax(const uint4 (&raw)[8])
+{
+    uint32_t pm = 0;
+#pragma unroll
+    for (int it = 0; it < 8; it++)
+        pm = pk_max_u16(pm, pk_max_u16(pk_max_u16(raw[it].x & kMagMask, raw[it].y & kMagMask),
+                                       pk_max_u16(raw[it].z & kMagMask, raw[it].w & kMagMask)));
+    const uint32_t lo = pm & 0xFFFFu, hi = pm >> 16;
+    return lo > hi ? lo : hi;
+}
+
+// Exponents and codes of one 128 x 128 tile from the registers that hold it.  With COL the body
+// contains one workgroup barrier, and the staging buffer tt stays in use until the next one.
+template <bool ROW, bool COL, bool CEIL>
+__device__ __forceinline__ void quant_tile_body(const uint4 (&raw)[8], const TileShape &sh, int64_t r0, int64_t c0,
+                                                const GlobalScale &g, uint8_t *__restrict__ q_row,
+                                                uint8_t *__restrict__ e_row, uint8_t *__restrict__ q_col,
+                                                uint8_t *__restrict__ e_col, uint8_t (*tt)[kTilePitch])
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane >> 4, ch = lane & 15;
+    const int64_t rows = sh.rows, cols = sh.cols;
+    const int64_t col = c0 + ch * 8;
+    const int64_t rbase = r0 + wave * kGroup + rl * 8;           // first of this lane's 8 rows
+    const bool ok = col < cols && rbase < rows;                  // cols % 32 == 0: whole column chunks
+    const int64_t left = rows - rbase;
+    const int n_ok = !ok ? 0 : (left < 8 ? (int)left : 8);       // (always 0 or 8 with COL: rows % 32 == 0)
+    const int64_t n_rgroups = rows / kGroup, n_cgroups = cols / kGroup;
+
+    // group maxima: a row group (32 columns of one row) lives in a quad of lanes; a column
+    // group in this lane's 8 rows and those of the lanes 16, 32 and 48 further on
+    uint32_t pm[4] = {0, 0, 0, 0};
+    float rf[8], cf[8];
+    uint32_t rbytes[2] = {0, 0}, cbytes[2] = {0, 0};
+    bool wide = false;
+#pragma unroll
+    for (int it = 0; it < 8; it++) {
+        const uint32_t m0 = raw[it].x & kMagMask, m1 = raw[it].y & kMagMask, m2 = raw[it].z & kMagMask,
+                       m3 = raw[it].w & kMagMask;
+        if (COL) {
+            pm[0] = pk_max_u16(pm[0], m0);
+            pm[1] = pk_max_u16(pm[1], m1);
+            pm[2] = pk_max_u16(pm[2], m2);
+            pm[3] = pk_max_u16(pm[3], m3);
+        }
+        if (ROW) {
+            const uint32_t p = pk_max_u16(pk_max_u16(m0, m1), pk_max_u16(m2, m3));
+            const uint32_t lo = p & 0xFFFFu, hi = p >> 16;
+            const uint32_t gmax = quad_max_u32(lo > hi ? lo : hi);
+            const int ex = local_exponent<CEIL>(gmax, g);
+            rf[it] = group_factor(gmax, ex, g);
+            wide |= factor_is_wide(rf[it]);
+            rbytes[it >> 2] |= (uint32_t)(ex + 127) << (8 * (it & 3));
+        }
+    }
+    if (COL) {
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 16, 64));
+            pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 32, 64));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const uint32_t m = (pm[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+            const int ex = local_exponent<CEIL>(m, g);
+            cf[j] = group_factor(m, ex, g);
+            wide |= factor_is_wide(cf[j]);
+            cbytes[j >> 2] |= (uint32_t)(ex + 127) << (8 * (j & 3));
+        }
+    }
+
+    if (ROW && (lane & 3) == 0) {
+#pragma unroll
+        for (int it = 0; it < 8; it++)
+            if (it < n_ok) e_row[(rbase + it) * n_cgroups + (col >> 5)] = (uint8_t)(rbytes[it >> 2] >> (8 * (it & 3)));
+    }
+    if (COL && ok && rl == 0) {
+        const int64_t gidx = (r0 >> 5) + wave;
+#pragma unroll
+        for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
+    }
+
+    uint32_t pieces[8][2];
+#pragma unroll
+    for (int j = 0; j < 8; j++) pieces[j][0] = pieces[j][1] = 0;
+    uint8_t *q_row_lane = ROW ? q_row + rbase * cols + col : nullptr;
+    if (__any(wide)) {
+        WideTile w;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            w.raw[i] = raw[i];
+            w.rf[i] = ROW ? rf[i] : 0.0f;
+            w.cf[i] = COL ? cf[i] : 0.0f;
+            w.pieces[i][0] = w.pieces[i][1] = 0;
+        }
+        w.rbytes[0] = rbytes[0]; w.rbytes[1] = rbytes[1];
+        w.cbytes[0] = cbytes[0]; w.cbytes[1] = cbytes[1];
+        w.inv_s = g.inv_s; w.n_ok = n_ok; w.q_row_lane = q_row_lane; w.cols = cols;
+        tile_codes_wide<ROW, COL>(&w);
+#pragma unroll
+        for (int j = 0; j < 8; j++) { pieces[j][0] = w.pieces[j][0]; pieces[j][1] = w.pieces[j][1]; }
+    } else {
+        tile_codes<ROW, COL, true>(raw, rf, rbytes, cf, cbytes, g.inv_s, n_ok, q_row_lane, cols, pieces);
+    }
+    if (!COL) return;
+
+    // the 8 rows of this lane form one 8-byte piece of each of its 8 transposed rows
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+        *reinterpret_cast<uint2 *>(&tt[ch * 8 + j][wave * kGroup + rl * 8]) = make_uint2(pieces[j][0], pieces[j][1]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int idx = tid + k * kQuantThreads, c = idx >> 3, piece = idx & 7;
+        if (c0 + c < cols && r0 + piece * 16 < rows) {
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(&tt[c][piece * 16]);
+            st_stream16(q_col + (c0 + c) * rows + r0 + piece * 16, make_uint4(src[0], src[1], src[2], src[3]));
         }
     }
 }
@@ -314,101 +486,207 @@ __global__ __launch_bounds__(kQuantThreads, 4) void k_quant_tile(const uint16_t 
     const GlobalScale g = fold_global_scale(partial, n_partial, red);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *s_global = g.s;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane >> 4, ch = lane & 15;
+    const TileShape sh = {rows, cols, ld};
     const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
-    const int64_t col = c0 + ch * 8;
-    const int64_t rbase = r0 + wave * kGroup + rl * 8;           // first of this lane's 8 rows
-    const bool ok = col < cols && rbase < rows;                  // cols % 32 == 0, rows % 32 == 0: whole groups
-    const int64_t n_rgroups = rows / kGroup, n_cgroups = cols / kGroup;
-
     uint4 raw[8];
-#pragma unroll
-    for (int it = 0; it < 8; it++) {
-        raw[it] = make_uint4(0, 0, 0, 0);
-        if (ok) raw[it] = ld_stream16(x + (rbase + it) * ld + col);
-    }
+    load_tile(raw, x, sh, r0, c0);
+    quant_tile_body<ROW, true, CEIL>(raw, sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
+}
 
-    // group maxima: a row group (32 columns of one row) lives in a quad of lanes; a column
-    // group in this lane's 8 rows and those of the lanes 16, 32 and 48 further on
-    uint32_t pm[4] = {0, 0, 0, 0};
-    float rf[8], cf[8];
-    uint32_t rbytes[2] = {0, 0}, cbytes[2] = {0, 0};
-    bool wide = false;
+// ---------------------------------------------------------------------------------------------
+// One-launch variant for tensors of up to kKeep tiles per workgroup of a co-resident grid (two
+// workgroups per compute unit; 64 MiB of BF16 on 256 compute units).  A workgroup loads its
+// tiles once and keeps them in registers between the maximum and the codes, so X is fetched
+// from memory once instead of twice: 128 KiB of registers per workgroup hold the tensor, the
+// other half of the register file does the arithmetic.
+//
+// Between the walks the workgroups agree on the global maximum through a few words of the
+// workspace.  Only relaxed device-scope atomics are used, no fences: a release or acquire fence
+// at device scope writes back / invalidates the whole L2 of the XCD and cost ~60 us per launch
+// here.  Everything that travels is a single word that carries its own validity:
+//   1. a workgroup merges its maximum into its group's word (atomic max) and only then -- the
+//      second atomic's operand depends on the first one's return value -- counts itself in;
+//   2. the workgroup that completes a group's count reads the group's word (all merges into it
+//      were performed before their senders counted in), merges it into the global word and
+//      counts the group in the same way;
+//   3. the workgroup that completes the count of groups reads the global word and publishes
+//      0x80000000 | maximum in one flag word per group, which the group's members poll.
+// The poll is bounded: a workgroup that does not see its flag within poll_limit polls (the grid
+// was not co-resident after all) computes the global maximum from X by itself, so every wave
+// ends whatever the scheduler does, and the outputs are the same either way.
+constexpr int kKeep = 4;
+constexpr uint32_t kPollLimit = 1u << 15;
+constexpr int kSyncGroups = 8;
+constexpr int kSyncStride = 32;                                    // words: every word on a 128-byte line of its own
+constexpr int kSyncWords = (3 * kSyncGroups + 2) * kSyncStride;    // group maxima, group counts, flags, global max, global count
+
+__global__ void k_quant_sync_reset(uint32_t *sync)
+{
+    for (int i = threadIdx.x; i < kSyncWords; i += blockDim.x) sync[i] = 0;
+}
+
+__device__ __forceinline__ uint32_t relaxed_load(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// v if `after` has arrived (it always has a value below 2^31 here): ties the issue of the next
+// atomic to the completion of the previous one without a fence
+__device__ __forceinline__ uint32_t after_value(uint32_t v, uint32_t after) { return v + (after >> 31); }
+
+template <bool ROW, bool COL, bool CEIL>
+__global__ __launch_bounds__(kQuantThreads, 2) void k_quant_persist(const uint16_t *__restrict__ x, int64_t rows,
+                                                                    int64_t cols, int64_t ld, int tiles_x, int n_tiles,
+                                                                    uint32_t *sync, uint32_t poll_limit,
+                                                                    uint8_t *__restrict__ q_row,
+                                                                    uint8_t *__restrict__ e_row,
+                                                                    uint8_t *__restrict__ q_col,
+                                                                    uint8_t *__restrict__ e_col,
+                                                                    float *__restrict__ s_global)
+{
+    __shared__ uint32_t red[kQuantThreads / kWave + 1];
+    __shared__ __attribute__((aligned(16))) uint8_t tt[kTile][kTilePitch];
+
+    const TileShape sh = {rows, cols, ld};
+    const int G = (int)gridDim.x, first = (int)blockIdx.x;
+    auto origin = [&](int t, int64_t &r0, int64_t &c0) {
+        const int ty = t / tiles_x;
+        r0 = (int64_t)ty * kTile;
+        c0 = (int64_t)(t - ty * tiles_x) * kTile;
+    };
+
+    // a workgroup's (up to kKeep) tiles are neighbours in a tile row: up to 1 KiB of every row of X in one place
+    const int per_group = (n_tiles + G - 1) / G;
+    auto kept_tile = [&](int k) { return k < per_group ? first * per_group + k : n_tiles; };
+    // walk 1: maximum of |x| over this workgroup's tiles
+    uint4 keep[kKeep][8];
+    uint32_t m = 0;
 #pragma unroll
-    for (int it = 0; it < 8; it++) {
-        const uint32_t m0 = raw[it].x & kMagMask, m1 = raw[it].y & kMagMask, m2 = raw[it].z & kMagMask,
-                       m3 = raw[it].w & kMagMask;
-        pm[0] = pk_max_u16(pm[0], m0);
-        pm[1] = pk_max_u16(pm[1], m1);
-        pm[2] = pk_max_u16(pm[2], m2);
-        pm[3] = pk_max_u16(pm[3], m3);
-        if (ROW) {
-            const uint32_t p = pk_max_u16(pk_max_u16(m0, m1), pk_max_u16(m2, m3));
-            const uint32_t lo = p & 0xFFFFu, hi = p >> 16;
-            const uint32_t gmax = quad_max_u32(lo > hi ? lo : hi);
-            const int ex = local_exponent<CEIL>(gmax, g);
-            rf[it] = group_factor(gmax, ex, g);
-            wide |= factor_is_wide(rf[it]);
-            rbytes[it >> 2] |= (uint32_t)(ex + 127) << (8 * (it & 3));
+    for (int k = 0; k < kKeep; k++) {
+        const int t = kept_tile(k);
+        if (t < n_tiles) {
+            int64_t r0, c0;
+            origin(t, r0, c0);
+            load_tile(keep[k], x, sh, r0, c0);
+        } else {
+#pragma unroll
+            for (int it = 0; it < 8; it++) keep[k][it] = make_uint4(0, 0, 0, 0);
         }
     }
 #pragma unroll
-    for (int d = 0; d < 4; d++) {
-        pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 16, 64));
-        pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 32, 64));
+    for (int k = 0; k < kKeep; k++) {
+        const uint32_t c = tile_absmax(keep[k]);
+        m = c > m ? c : m;
     }
-#pragma unroll
-    for (int j = 0; j < 8; j++) {
-        const uint32_t m = (pm[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-        const int ex = local_exponent<CEIL>(m, g);
-        cf[j] = group_factor(m, ex, g);
-        wide |= factor_is_wide(cf[j]);
-        cbytes[j >> 2] |= (uint32_t)(ex + 127) << (8 * (j & 3));
-    }
-
-    if (ok) {
-        if (ROW && (lane & 3) == 0) {
-#pragma unroll
-            for (int it = 0; it < 8; it++)
-                e_row[(rbase + it) * n_cgroups + (col >> 5)] = (uint8_t)(rbytes[it >> 2] >> (8 * (it & 3)));
-        }
-        if (rl == 0) {
-            const int64_t gidx = (r0 >> 5) + wave;
-#pragma unroll
-            for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
-        }
-    }
-
-    uint32_t pieces[8][2];
-#pragma unroll
-    for (int j = 0; j < 8; j++) pieces[j][0] = pieces[j][1] = 0;
-    uint8_t *q_row_lane = ROW ? q_row + rbase * cols + col : nullptr;
-    if (__any(wide))
-        tile_codes<ROW, false>(raw, rf, rbytes, cf, cbytes, g.inv_s, ok, q_row_lane, cols, pieces);
-    else
-        tile_codes<ROW, true>(raw, rf, rbytes, cf, cbytes, g.inv_s, ok, q_row_lane, cols, pieces);
-
-    // the 8 rows of this lane form one 8-byte piece of each of its 8 transposed rows
-#pragma unroll
-    for (int j = 0; j < 8; j++)
-        *reinterpret_cast<uint2 *>(&tt[ch * 8 + j][wave * kGroup + rl * 8]) = make_uint2(pieces[j][0], pieces[j][1]);
+    // meeting point
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
     __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < kQuantThreads / kWave; i++) m = red[i] > m ? red[i] : m;
+        uint32_t *grp_max = sync, *grp_cnt = sync + kSyncGroups * kSyncStride, *flags = sync + 2 * kSyncGroups * kSyncStride;
+        uint32_t *all_max = sync + 3 * kSyncGroups * kSyncStride, *all_cnt = all_max + kSyncStride;
+        const int grp = first % kSyncGroups, n_grp = G < kSyncGroups ? G : kSyncGroups;
+        const uint32_t members = (uint32_t)((G - grp + kSyncGroups - 1) / kSyncGroups);
+        uint32_t old = atomicMax(&grp_max[grp * kSyncStride], m);
+        if (atomicAdd(&grp_cnt[grp * kSyncStride], after_value(1u, old)) == members - 1) {
+            const uint32_t gm = atomicMax(&grp_max[grp * kSyncStride], 0u);     // an atomic read of the group's word
+            old = atomicMax(all_max, gm);
+            if (atomicAdd(all_cnt, after_value(1u, old)) == (uint32_t)n_grp - 1) {
+                const uint32_t am = atomicMax(all_max, 0u);
+                for (int i = 0; i < n_grp; i++)
+                    __hip_atomic_store(&flags[i * kSyncStride], 0x80000000u | am, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        uint32_t polls = 0, flag;
+        while (true) {
+            flag = relaxed_load(&flags[grp * kSyncStride]);
+            if (flag != 0 || polls >= poll_limit) break;
+            polls++;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        red[kQuantThreads / kWave] = flag;
+    }
+    __syncthreads();
+    uint32_t amax_bits = red[kQuantThreads / kWave];
+    if (amax_bits != 0) {
+        amax_bits &= 0x7FFFu;
+    } else {
+        // the flag did not come in time: take the maximum over all of X here
+        uint32_t mm = 0;
+        for (int t = 0; t < n_tiles; t++) {
+            uint4 ra[8];
+            int64_t r0, c0;
+            origin(t, r0, c0);
+            load_tile(ra, x, sh, r0, c0);
+            const uint32_t c = tile_absmax(ra);
+            mm = c > mm ? c : mm;
+        }
+        mm = wave_max_u32(mm);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mm;
+        __syncthreads();
+        amax_bits = red[0];
+        for (int i = 1; i < kQuantThreads / kWave; i++) amax_bits = red[i] > amax_bits ? red[i] : amax_bits;
+    }
+    const GlobalScale g = make_global_scale(amax_bits);
+    if (first == 0 && threadIdx.x == 0) *s_global = g.s;
+
+    // walk 2: codes and exponents from the registers
 #pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int idx = tid + k * kQuantThreads, c = idx >> 3, piece = idx & 7;
-        if (c0 + c < cols && r0 + piece * 16 < rows) {
-            const uint32_t *src = reinterpret_cast<const uint32_t *>(&tt[c][piece * 16]);
-            st_stream16(q_col + (c0 + c) * rows + r0 + piece * 16, make_uint4(src[0], src[1], src[2], src[3]));
+    for (int k = 0; k < kKeep; k++) {
+        const int t = kept_tile(k);
+        if (t < n_tiles) {
+            int64_t r0, c0;
+            origin(t, r0, c0);
+            quant_tile_body<ROW, COL, CEIL>(keep[k], sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
+            if (COL) __syncthreads();
         }
     }
 }
 
 }  // namespace moss
 
+namespace {
+
+std::atomic<uint32_t> g_poll_limit{moss::kPollLimit};
+
+using PersistFn = void (*)(const uint16_t *, int64_t, int64_t, int64_t, int, int, uint32_t *, uint32_t, uint8_t *, uint8_t *,
+                           uint8_t *, uint8_t *, float *);
+
+PersistFn persist_kernel(bool row, bool col, bool ceil_mode)
+{
+    using namespace moss;
+    if (row && col) return ceil_mode ? k_quant_persist<true, true, true> : k_quant_persist<true, true, false>;
+    if (col) return ceil_mode ? k_quant_persist<false, true, true> : k_quant_persist<false, true, false>;
+    return ceil_mode ? k_quant_persist<true, false, true> : k_quant_persist<true, false, false>;
+}
+
+// Workgroups of the one-launch kernel that one compute unit holds at a time, at most 2 (0: do not use it).
+int persist_groups_per_cu(PersistFn fn, int variant)
+{
+    static std::atomic<int> cached[8] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
+    int v = cached[variant].load();
+    if (v < 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void *>(fn), moss::kQuantThreads, 0) !=
+            hipSuccess) {
+            (void)hipGetLastError();
+            n = 0;
+        }
+        v = n > 2 ? 2 : n;
+        cached[variant].store(v);
+    }
+    return v;
+}
+
+}  // namespace
+
+extern "C" void moss_quant_set_poll_limit(unsigned polls) { g_poll_limit.store(polls); }
+
 extern "C" size_t moss_quant_workspace_bytes(int64_t rows, int64_t cols, unsigned flags)
 {
     (void)rows; (void)cols; (void)flags;
-    return (size_t)moss::kMaxPartials * sizeof(uint32_t);
+    return (size_t)(moss::kMaxPartials + moss::kSyncWords) * sizeof(uint32_t);
 }
 
 extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
@@ -437,6 +715,26 @@ extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t c
     const int chunks_per_row = (int)(cols / 8);
     const int64_t n_chunks = rows * chunks_per_row;
     const int dense = (ld == cols);
+
+    // Tensors of one to kKeep tiles per workgroup: one launch that keeps X in registers between the
+    // maximum and the codes.
+    {
+        const int64_t tiles_x = (cols + kTile - 1) / kTile, tiles_y = (rows + kTile - 1) / kTile;
+        const int64_t n_tiles = tiles_x * tiles_y;
+        const int variant = (want_row ? 1 : 0) | (want_col ? 2 : 0) | (ceil_mode ? 4 : 0);
+        PersistFn fn = persist_kernel(want_row, want_col, ceil_mode);
+        const int per_cu = persist_groups_per_cu(fn, variant);
+        const int64_t grid = (int64_t)per_cu * moss_internal_cu_count();
+        if (per_cu > 0 && n_tiles >= grid && n_tiles <= grid * kKeep) {
+            uint32_t *sync = partial + kMaxPartials;
+            hipLaunchKernelGGL(k_quant_sync_reset, dim3(1), dim3(kQuantThreads), 0, st, sync);
+            MOSS_LAUNCH_CHECK();
+            hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(kQuantThreads), 0, st, x, rows, cols, ld, (int)tiles_x,
+                               (int)n_tiles, sync, g_poll_limit.load(), q_row, e_row, q_col, e_col, s_global);
+            MOSS_LAUNCH_CHECK();
+            return MOSS_OK;
+        }
+    }
 
     int64_t want_blocks = (n_chunks + kQuantThreads * kAmaxUnroll - 1) / (kQuantThreads * kAmaxUnroll);
     const int n_partial = (int)(want_blocks < kMaxPartials ? want_blocks : kMaxPartials);

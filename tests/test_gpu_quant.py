@@ -72,10 +72,38 @@ def test_ragged_shapes(oracle, shape):
     check_against_oracle(oracle, xb, 0, f"ragged {shape}")
 
 
-@pytest.mark.parametrize("shape,flag", [((4128, 2080), 0), ((4133, 2080), CEIL), ((1056, 8352), 0)])
+# Tensors with at least two 128 x 128 tiles per compute unit take the one-launch kernel (a bounded
+# grid that meets once for the global maximum and keeps its first tiles in registers).
+@pytest.mark.parametrize("shape,flag", [((4128, 2080), 0),      # ragged edges, every tile kept
+                                        ((4133, 2080), CEIL),   # rows not a multiple of 8: row grouping only
+                                        ((1056, 8352), 0),      # (fewer tiles: the two-launch path)
+                                        ((4128, 8352), 0),      # a few workgroups fetch a fifth tile again
+                                        ((8224, 7200), CEIL)])  # several tiles per workgroup beyond the kept ones
 def test_many_tiles_with_ragged_edges(oracle, shape, flag):
     xb = mi.heavy_tailed_activation(shape[0], shape[1], seed=40 + shape[1])
     check_against_oracle(oracle, xb, flag, f"many tiles {shape}")
+
+
+def test_one_launch_path_when_the_meeting_times_out(oracle):
+    # poll limit 0: every workgroup that finds the maximum not yet published computes it by itself
+    xb = mi.heavy_tailed_activation(4128, 2080, seed=47)
+    moss.quant_set_poll_limit(0)
+    try:
+        check_against_oracle(oracle, xb, 0, "one-launch, no polling")
+    finally:
+        moss.quant_set_poll_limit(32768)
+
+
+def test_one_launch_path_reuses_a_dirty_workspace(oracle):
+    xb = mi.heavy_tailed_activation(4128, 2080, seed=48)
+    x = bf16_to_gpu(xb)
+    ws = torch.full((1 << 15,), 0xFF, dtype=torch.uint8, device=x.device)
+    qr, er, s = oracle.quant_act_2level(xb, 0, 0)
+    for _ in range(2):
+        got = moss.quant_act_2level(x, ROW | COL, workspace=ws)
+        torch.cuda.synchronize()
+        assert scalar(got["s"]) == s
+        assert np.array_equal(u8(got["q_row"]), qr) and np.array_equal(u8(got["e_row"]), er)
 
 
 def test_row_stride_larger_than_cols(oracle):
