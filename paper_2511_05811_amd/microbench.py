@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Side tables of the paper re-measured on one MI355X with the library's own kernels.
+
+    python -m paper_2511_05811_amd.microbench scaling   # Table "Time usage to calculate per-tensor scaling factors" (Sec. 3.2)
+                                                         # and the interval sweep of the scaling ablation (App.)
+    python -m paper_2511_05811_amd.microbench gemm      # Table "Runtime of quantized FP8 GEMM" (Sec. 4.3): its seven shapes
+    python -m paper_2511_05811_amd.microbench snr       # Sec. 3.1 Eq. 3 / SNR table: per-tensor vs two-level microscaling
+
+Each mode prints one JSON line.  Inputs are seeded and synthetic; the paper's own figures are
+quoted with the hardware they were measured on, as context only.  Everything that is timed
+runs in the HIP library; torch supplies memory, streams, events and the FP64 arithmetic of
+the SNR evaluation.
+"""
+import argparse
+import json
+import sys
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def _time_ms(torch, fn, reps, warmup=2):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = _events(torch)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ts.sort()
+    return ts[len(ts) // 2], ts[0]
+
+
+def _adamw_args(moss, t, interval):
+    import numpy as np
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.95))
+    return moss.AdamWArgs(3e-4, 0.9, 0.95, 1e-8, 0.1, 1.0 - b1, 1.0 - b2, 1.0 - b1 ** t, 1.0 - b2 ** t, 1.0, interval, t)
+
+
+# Sec. 3.2, table of scaling-factor time: tensor sizes and the paper's H800 figures (ms)
+SCALING_SIZES = [((11008, 16384), 0.54, 0.02), ((11008, 8192), 0.32, 0.02), ((4096, 12288), 0.17, 0.02), ((4096, 4096), 0.08, 0.02)]
+
+
+def scaling(moss, torch, small=False):
+    """Per step, just-in-time scaling costs a max-reduction before the cast; here that is the
+    step with `interval = 1` (AdamW pass that yields amax, then a second pass that casts with
+    the fresh scale).  Automatic scaling predicts the scale from the learning rates, so the
+    cast is fused into the one AdamW pass and the scale itself costs a few scalar operations
+    inside the kernel that finalises the step."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(40)
+    rows_out = []
+    sizes = [((1024, 2048), None, None)] if small else SCALING_SIZES
+    for (r, c), paper_jit, paper_auto in sizes:
+        w = torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32) * 0.02
+        m = torch.zeros_like(w); v = torch.zeros_like(w)
+        g = torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32) * 1e-3
+        wq = torch.empty((r, c), dtype=torch.uint8, device=dev)
+        state = moss.new_wscale_state(dev)
+        ws = torch.empty(max(16, moss.load().moss_weight_workspace_bytes(r, c)), dtype=torch.uint8, device=dev)
+        moss.weight_autoscale_init(w, state, wq=wq, workspace=ws)
+        step = [0]
+
+        def one(interval):
+            step[0] += 1
+            moss.weight_autoscale_cast(w, m, v, g, _adamw_args(moss, step[0], interval), state, wq=wq, workspace=ws)
+
+        auto_ms, _ = _time_ms(torch, lambda: one(0), 8 if small else 12)
+        jit_ms, _ = _time_ms(torch, lambda: one(1), 8 if small else 12)
+        # the max-reduction alone, as a separate pass over the FP32 weights (what a non-fused
+        # just-in-time cast adds): initialisation = max-reduction + cast, minus the cast pass
+        init_ms, _ = _time_ms(torch, lambda: moss.weight_autoscale_init(w, state, wq=wq, workspace=ws), 8)
+        rows_out.append({"rows": r, "cols": c, "fused_step_auto_ms": round(auto_ms, 4), "step_with_max_reduction_ms": round(jit_ms, 4),
+                         "jit_extra_ms_per_step": round(jit_ms - auto_ms, 4), "amax_plus_cast_ms": round(init_ms, 4),
+                         "paper_h800_jit_ms": paper_jit, "paper_h800_auto_ms": paper_auto})
+        del w, m, v, g, wq
+    # interval sweep: amortised cost of the periodic max-reduction and how close the predicted
+    # scale stays to the exact one (ratio >= 1 means no overflow is possible)
+    sweep = []
+    r, c = (512, 1024) if small else (4096, 11008)
+    steps = 40 if small else 400
+    for interval in ([10, 20] if small else [100, 500, 2000]):
+        gen.manual_seed(41)
+        w = torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32) * 0.02
+        m = torch.zeros_like(w); v = torch.zeros_like(w)
+        wq = torch.empty((r, c), dtype=torch.uint8, device=dev)
+        state = moss.new_wscale_state(dev)
+        ws = torch.empty(max(16, moss.load().moss_weight_workspace_bytes(r, c)), dtype=torch.uint8, device=dev)
+        moss.weight_autoscale_init(w, state, wq=wq, workspace=ws)
+        worst = 1e30
+        for t in range(1, steps + 1):
+            g = torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32) * 1e-3
+            moss.weight_autoscale_cast(w, m, v, g, _adamw_args(moss, t, interval), state, wq=wq, workspace=ws)
+            if t % (steps // 8) == 0:
+                st = moss.read_wscale_state(state)
+                worst = min(worst, st.s_cur / (st.amax_seen / 448.0))
+        st = moss.read_wscale_state(state)
+        g = torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32) * 1e-3
+        tt = [steps]
+
+        def one_more(iv):
+            tt[0] += 1
+            moss.weight_autoscale_cast(w, m, v, g, _adamw_args(moss, tt[0], iv), state, wq=wq, workspace=ws)
+
+        extra = _time_ms(torch, lambda: one_more(1), 6)[0] - _time_ms(torch, lambda: one_more(0), 6)[0]
+        sweep.append({"interval": interval, "steps": steps, "overflow_count": int(st.overflow_count),
+                      "min_predicted_over_exact_scale": round(worst, 4),
+                      "amortised_max_reduction_ms_per_step": round(extra / interval, 5)})
+        del w, m, v, wq
+    return {"table": "scaling", "unit": "ms", "sizes": rows_out, "interval_sweep": sweep,
+            "note": "paper figures: NVIDIA H800, context only"}
+
+
+# Sec. 4.3, table of quantized FP8 GEMM runtime: (M, N, K) and the paper's MOSS time on H800 (ms)
+GEMM_SHAPES = [((2048, 7168, 4096), 0.25), ((2048, 7168, 11008), 0.67), ((4096, 2048, 7168), 0.45), ((4096, 4096, 8192), 0.60),
+               ((4096, 4096, 12288), 0.72), ((5120, 5120, 10240), 1.04), ((8192, 8192, 8192), 1.98)]
+
+
+def gemm(moss, torch, small=False):
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(42)
+    out_rows = []
+    shapes = [((512, 768, 512), None)] if small else GEMM_SHAPES
+    for (M, N, K), paper_ms in shapes:
+        x = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        w = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        qx = moss.quant_act_2level(x, moss.MOSS_Q_ROW)
+        state = moss.new_wscale_state(dev)
+        wq, _ = moss.weight_autoscale_init(w, state)
+        s_w = state[4:8].view(torch.float32)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ms, best = _time_ms(torch, lambda: moss.gemm_fp8_mx(qx["q_row"], qx["e_row"], qx["s"], wq, None, s_w, out=y), 10)
+        bf_ms, _ = _time_ms(torch, lambda: moss.gemm_bf16_baseline(x, w, out=y), 5)
+        q_ms, _ = _time_ms(torch, lambda: moss.quant_act_2level(x, moss.MOSS_Q_ROW, out=qx), 5)
+        out_rows.append({"M": M, "N": N, "K": K, "fp8_mx_ms": round(ms, 4), "fp8_mx_tflops": round(2.0 * M * N * K / ms / 1e9, 1),
+                         "bf16_hand_gemm_ms": round(bf_ms, 4), "quant_x_ms": round(q_ms, 4), "paper_h800_moss_ms": paper_ms})
+    return {"table": "gemm_shapes", "rows": out_rows, "note": "GEMM alone, operands already quantized; paper figures: NVIDIA H800, context only"}
+
+
+def _e4m3_table(torch, dev):
+    """Value of every E4M3 code (OCP E4M3: bias 7, no infinities, 0x7F / 0xFF are NaN), FP64."""
+    codes = torch.arange(256, device=dev)
+    sign = torch.where(codes >= 128, -1.0, 1.0).double()
+    ex = ((codes >> 3) & 15).double()
+    man = (codes & 7).double()
+    val = torch.where(ex == 0, man / 8.0 * 2.0 ** -6, (1.0 + man / 8.0) * torch.pow(torch.tensor(2.0, device=dev, dtype=torch.float64), ex - 7.0))
+    return sign * val
+
+
+def snr(moss, torch, small=False):
+    """SNR = 10 log10(sum x^2 / sum (x - DQ(Q(x)))^2) (Sec. 3.1, Eq. 3) of the library's codes on
+    heavy-tailed activations with outlier channels; the per-tensor row uses the library's
+    per-tensor cast (the weight path's initialisation) on the same tensor."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(43)
+    rows, cols = (256, 512) if small else (8192, 4096)
+    # Student-t(3) x 0.5 = normal / sqrt(chi2_3 / 3); 1 % of the channels x 100
+    z = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32)
+    chi = sum(torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) ** 2 for _ in range(3))
+    x = 0.5 * z / torch.sqrt(chi / 3.0)
+    idx = torch.randperm(cols, generator=gen, device=dev)[: max(1, cols // 100)]
+    x[:, idx] *= 100.0
+    xb = x.to(torch.bfloat16)
+    xd = xb.double()
+    table = _e4m3_table(torch, dev)
+    power = float((xd * xd).sum())
+
+    def snr_db(deq):
+        return float(10.0 * torch.log10(torch.tensor(power) / float(((xd - deq) ** 2).sum())))
+
+    out = {}
+    for name, flag in (("moss_nearest", 0), ("moss_ceil", moss.MOSS_EXP_CEIL)):
+        q = moss.quant_act_2level(xb, moss.MOSS_Q_ROW | flag)
+        ss = torch.pow(torch.tensor(2.0, device=dev, dtype=torch.float64), q["e_row"].double() - 127.0)
+        deq = table[q["q_row"].long()] * float(q["s"][0]) * ss.repeat_interleave(32, dim=1)
+        out[name] = round(snr_db(deq), 2)
+        nonout = torch.ones(cols, dtype=torch.bool, device=dev); nonout[idx] = False
+        e = ((xd - deq) ** 2)[:, nonout].sum()
+        out[name + "_non_outlier_channels"] = round(float(10.0 * torch.log10((xd * xd)[:, nonout].sum() / e)), 2)
+    state = moss.new_wscale_state(dev)
+    wq, _ = moss.weight_autoscale_init(xb, state)
+    s = float(state[4:8].view(torch.float32)[0])
+    deq = table[wq.long()] * s
+    out["per_tensor"] = round(snr_db(deq), 2)
+    nonout = torch.ones(cols, dtype=torch.bool, device=dev); nonout[idx] = False
+    out["per_tensor_non_outlier_channels"] = round(float(10.0 * torch.log10((xd * xd)[:, nonout].sum() / ((xd - deq) ** 2)[:, nonout].sum())), 2)
+    return {"table": "snr", "unit": "dB", "shape": [rows, cols], "snr": out,
+            "note": "paper (activations of a trained 7B model): two-level 3.0-3.4 dB above per-group-128, 9.2-9.4 dB above per-tensor; "
+                    "synthetic heavy-tailed tensors stand in, so only the ordering is comparable.  moss_nearest rounds the local exponent "
+                    "to the closest power of two as Eq. 2 prints it, which lets a group maximum exceed 448 by up to sqrt(2) and "
+                    "saturate; moss_ceil rounds it up and never clips"}
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("table", choices=["scaling", "gemm", "snr"])
+    ap.add_argument("--small", action="store_true", help="tiny shapes (used by the tests)")
+    a = ap.parse_args(argv)
+    import torch
+    import paper_2511_05811_amd as moss
+    if not torch.cuda.is_available():
+        print("microbench needs the MI355X", file=sys.stderr)
+        return 2
+    res = {"scaling": scaling, "gemm": gemm, "snr": snr}[a.table](moss, torch, a.small)
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
