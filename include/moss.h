@@ -91,7 +91,11 @@ int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_
  * maximum from X by itself, so the kernel ends even if its workgroups cannot all run at once;
  * the outputs are the same on either path.  Process-wide, takes effect from the next call; the
  * default is 32768.  0 makes every workgroup that finds the result not yet published take the
- * slow path (used by the tests). */
+ * slow path (used by the tests).  The one-launch kernel assumes the device to itself: when other
+ * kernels occupy compute units at the same time (calls on several streams at once) part of its
+ * grid may have to wait for them, and workgroups then fall back to the slow path after the
+ * bound -- correct, but slow; quantizer calls that must overlap other work should be
+ * serialised on one stream. */
 void moss_quant_set_poll_limit(unsigned polls);
 
 /* ---------------------------------------------------------------------------
