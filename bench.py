@@ -172,7 +172,7 @@ def main():
                          "against which hardware byte counters can be scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, 'How it would shard').")
+        log("bench.py measures one GPU only: this build has no multi-GPU path; run it with --gpus 1.")
         sys.exit(2)
 
     import torch

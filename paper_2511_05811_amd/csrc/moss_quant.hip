@@ -260,7 +260,8 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
 //    transposed output row; the pieces are collected in LDS and, after the only barrier,
 //    8 lanes write the 128 bytes of each transposed row.
 constexpr int kTile = 128;
-constexpr int kTilePitch = kTile + 8;   // bytes per staged output row (8-byte aligned pieces, some bank spread)
+constexpr int kTilePitch = kTile + 8;   // bytes per staged output row (8-byte aligned pieces, some bank spread; the
+                                        // spare bytes carry the column exponents)
 
 // Codes of one lane's 8 x 8 values for both groupings.  Rows are taken two at a time: the
 // converter packs two values into two neighbouring bytes, so feeding it the same column
@@ -366,7 +367,9 @@ __device__ __forceinline__ uint32_t tile_absmax(const uint4 (&raw)[8])
 
 // Exponents and codes of one 128 x 128 tile from the registers that hold it.  With COL the body
 // contains one workgroup barrier, and the staging buffer tt stays in use until the next one.
-template <bool ROW, bool COL, bool CEIL>
+// STAGE_E: the column exponents leave through LDS as 4-byte stores (see below); the one-launch
+// kernel, which holds its tiles in registers and has none to spare, stores them byte by byte.
+template <bool ROW, bool COL, bool CEIL, bool STAGE_E>
 __device__ __forceinline__ void quant_tile_body(const uint4 (&raw)[8], const TileShape &sh, int64_t r0, int64_t c0,
                                                 const GlobalScale &g, uint8_t *__restrict__ q_row,
                                                 uint8_t *__restrict__ e_row, uint8_t *__restrict__ q_col,
@@ -428,10 +431,19 @@ __device__ __forceinline__ void quant_tile_body(const uint4 (&raw)[8], const Til
         for (int it = 0; it < 8; it++)
             if (it < n_ok) e_row[(rbase + it) * n_cgroups + (col >> 5)] = (uint8_t)(rbytes[it >> 2] >> (8 * (it & 3)));
     }
-    if (COL && ok && rl == 0) {
-        const int64_t gidx = (r0 >> 5) + wave;
+    // The exponent bytes of a column's four row groups in this tile are neighbours in e_col: they are
+    // collected in the 8 spare bytes of the staging rows and go out as one 4-byte store per column
+    // (single-byte stores from every wave cost four times the cache-line visits).
+    const bool whole_groups = STAGE_E && (rows & (kTile - 1)) == 0;    // all four row groups of every tile exist
+    if (COL && rl == 0) {
+        if (whole_groups) {
 #pragma unroll
-        for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
+            for (int j = 0; j < 8; j++) tt[ch * 8 + j][kTile + wave] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
+        } else if (ok) {
+            const int64_t gidx = (r0 >> 5) + wave;
+#pragma unroll
+            for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
+        }
     }
 
     uint32_t pieces[8][2];
@@ -471,6 +483,9 @@ __device__ __forceinline__ void quant_tile_body(const uint4 (&raw)[8], const Til
             st_stream16(q_col + (c0 + c) * rows + r0 + piece * 16, make_uint4(src[0], src[1], src[2], src[3]));
         }
     }
+    if (whole_groups && tid < kTile && c0 + tid < cols)
+        *reinterpret_cast<uint32_t *>(e_col + (c0 + tid) * n_rgroups + (r0 >> 5)) =
+            *reinterpret_cast<const uint32_t *>(&tt[tid][kTile]);
 }
 
 template <bool ROW, bool CEIL>
@@ -490,7 +505,7 @@ __global__ __launch_bounds__(kQuantThreads, 4) void k_quant_tile(const uint16_t 
     const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
     uint4 raw[8];
     load_tile(raw, x, sh, r0, c0);
-    quant_tile_body<ROW, true, CEIL>(raw, sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
+    quant_tile_body<ROW, true, CEIL, true>(raw, sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -638,7 +653,7 @@ __global__ __launch_bounds__(kQuantThreads, 2) void k_quant_persist(const uint16
         if (t < n_tiles) {
             int64_t r0, c0;
             origin(t, r0, c0);
-            quant_tile_body<ROW, COL, CEIL>(keep[k], sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
+            quant_tile_body<ROW, COL, CEIL, false>(keep[k], sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
             if (COL) __syncthreads();
         }
     }
