@@ -5,6 +5,8 @@
                                                          # and the interval sweep of the scaling ablation (App.)
     python -m paper_2511_05811_amd.microbench gemm      # Table "Runtime of quantized FP8 GEMM" (Sec. 4.3): its seven shapes
     python -m paper_2511_05811_amd.microbench snr       # Sec. 3.1 Eq. 3 / SNR table: per-tensor vs two-level microscaling
+    python -m paper_2511_05811_amd.microbench limits    # what the machine allows: GEMM rate and shader clock by operand
+                                                         # content (power limit), plain device-copy bandwidth
 
 Each mode prints one JSON line.  Inputs are seeded and synthetic; the paper's own figures are
 quoted with the hardware they were measured on, as context only.  Everything that is timed
@@ -199,9 +201,87 @@ def snr(moss, torch, small=False):
                     "saturate; moss_ceil rounds it up and never clips"}
 
 
+class _ClockPoller:
+    """Samples the shader clock with `rocm-smi --showclocks` (a child process that only reads sysfs)
+    while the GPU works."""
+
+    def __init__(self):
+        import threading
+        self.samples, self._stop = [], threading.Event()
+        self._t = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self._stop.is_set():
+            try:
+                out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
+                m = re.search(r"sclk clock level[^(]*\((\d+)Mhz\)", out)
+                if m:
+                    self.samples.append(int(m.group(1)))
+            except Exception:
+                return
+            self._stop.wait(0.2)
+
+    def __enter__(self):
+        self._t.start()
+        return self
+
+    def __exit__(self, *a):
+        self._stop.set()
+        self._t.join(timeout=15)
+
+
+def limits(moss, torch, small=False):
+    """The same GEMM binary on operands of different content: the matrix cores draw more power the
+    more operand bits toggle, and the clock follows.  Plus the bandwidth of a plain device copy as
+    the practical ceiling of a read+write stream."""
+    import time
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(44)
+    M = N = K = 1024 if small else 8192
+    secs = 0.3 if small else 3.0
+    one = torch.ones(1, dtype=torch.float32, device=dev)
+    out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    ae = torch.full((M, K // 32), 127, dtype=torch.uint8, device=dev)
+    x = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    w = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    qx, qw = moss.quant_act_2level(x, moss.MOSS_Q_ROW), moss.quant_act_2level(w, moss.MOSS_Q_ROW)
+    cases = [("constant codes (1.0)", torch.full((M, K), 0x38, dtype=torch.uint8, device=dev),
+              torch.full((N, K), 0x38, dtype=torch.uint8, device=dev), ae),
+             ("uniformly random codes", torch.randint(0, 120, (M, K), dtype=torch.uint8, device=dev, generator=gen),
+              torch.randint(0, 120, (N, K), dtype=torch.uint8, device=dev, generator=gen), ae),
+             ("quantized Gaussians", qx["q_row"], qw["q_row"], qx["e_row"])]
+    rows = []
+    for name, a, b, e in cases:
+        for _ in range(3):
+            moss.gemm_fp8_mx(a, e, one, b, None, one, out=out)
+        torch.cuda.synchronize()
+        n = 0
+        with _ClockPoller() as poll:
+            t0 = time.time()
+            while time.time() - t0 < secs:
+                for _ in range(20):
+                    moss.gemm_fp8_mx(a, e, one, b, None, one, out=out)
+                torch.cuda.synchronize()
+                n += 20
+            dt = time.time() - t0
+        clk = sorted(poll.samples[1:-1] or poll.samples)
+        rows.append({"operands": name, "us_per_gemm": round(dt / n * 1e6, 1), "tflops": round(2.0 * M * N * K * n / dt / 1e12, 1),
+                     "sclk_mhz_median": clk[len(clk) // 2] if clk else None, "sclk_samples": len(clk)})
+    copies = []
+    for mb in ([8] if small else [64, 1024]):
+        src = torch.empty(mb << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        ms, _ = _time_ms(torch, lambda: dst.copy_(src), 10)
+        copies.append({"mib": mb, "ms": round(ms, 4), "gbs_read_plus_write": round(2.0 * (mb << 20) / ms / 1e6, 1)})
+    return {"table": "limits", "gemm_shape": [M, N, K], "gemm_by_operand_content": rows, "device_copy": copies}
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["scaling", "gemm", "snr"])
+    ap.add_argument("table", choices=["scaling", "gemm", "snr", "limits"])
     ap.add_argument("--small", action="store_true", help="tiny shapes (used by the tests)")
     a = ap.parse_args(argv)
     import torch
@@ -209,7 +289,7 @@ def main(argv=None):
     if not torch.cuda.is_available():
         print("microbench needs the MI355X", file=sys.stderr)
         return 2
-    res = {"scaling": scaling, "gemm": gemm, "snr": snr}[a.table](moss, torch, a.small)
+    res = {"scaling": scaling, "gemm": gemm, "snr": snr, "limits": limits}[a.table](moss, torch, a.small)
     print(json.dumps(res))
     return 0
 

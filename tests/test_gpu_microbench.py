@@ -34,3 +34,9 @@ def test_snr_table_small():
     # rounding the exponent to the nearest power of two (Eq. 2 as printed) clips group maxima by up
     # to sqrt(2): its SNR is reported, not asserted
     assert res["moss_nearest"] > 10.0
+
+
+def test_limits_table_small():
+    res = microbench.limits(moss, torch, small=True)
+    assert len(res["gemm_by_operand_content"]) == 3 and all(r["tflops"] > 0 for r in res["gemm_by_operand_content"])
+    assert res["device_copy"][0]["gbs_read_plus_write"] > 0
