@@ -1,0 +1,188 @@
+"""One LLaMA-style decoder block training step with its linears on the MOSS FP8 path.
+
+This is measurement scaffolding around the library, not part of it: RMSNorm, rotary embedding,
+causal attention, SwiGLU and the residual adds are ordinary BF16 torch operations, identical in
+both arms of the comparison, exactly as the paper leaves them in BF16 (Sec. 4.1).  Only the
+linear layers differ:
+
+  arm "moss": X and dY are two-level quantized (both groupings in one call), the three GEMMs
+              run on the block-scaled FP8 matrix cores, the optimizer step is the fused
+              AdamW + automatic scaling + FP8 cast of the library;
+  arm "bf16": the same three GEMMs as BF16 torch matmuls, AdamW as torch's fused optimizer on
+              FP32 master weights followed by a BF16 copy.
+
+Q, K and V are one fused hidden -> 3 hidden linear; gate and up are separate linears.
+"""
+def _adamw_args(moss, t, lr=3e-4, interval=500):
+    import numpy as np
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.95))
+    return moss.AdamWArgs(lr, 0.9, 0.95, 1e-8, 0.1, 1.0 - b1, 1.0 - b2, 1.0 - b1 ** t, 1.0 - b2 ** t, 1.0, interval, t)
+
+
+class _MossLinear:
+    """FP32 master weight [N x K] with its FP8 copies, optimizer state and per-layer buffers."""
+
+    def __init__(self, moss, torch, tokens, k, n, gen, dev):
+        u8, f32 = torch.uint8, torch.float32
+        self.moss, self.k, self.n = moss, k, n
+        self.w = torch.randn((n, k), generator=gen, device=dev, dtype=f32) * 0.02
+        self.m = torch.zeros_like(self.w)
+        self.v = torch.zeros_like(self.w)
+        self.dw = torch.empty((n, k), dtype=f32, device=dev)
+        self.state = moss.new_wscale_state(dev)
+        self.wq = torch.empty((n, k), dtype=u8, device=dev)
+        self.wq_t = torch.empty((k, n), dtype=u8, device=dev)
+        lib = moss.load()
+        self.ws_w = torch.empty(max(16, lib.moss_weight_workspace_bytes(n, k)), dtype=u8, device=dev)
+        self.ws_q = torch.empty(max(16, lib.moss_quant_workspace_bytes(tokens, max(k, n), 3)), dtype=u8, device=dev)
+        moss.weight_autoscale_init(self.w, self.state, wq=self.wq, wq_t=self.wq_t, workspace=self.ws_w)
+        self.s_w = self.state[4:8].view(f32)
+
+        def qbuf(r, c):
+            return dict(q_row=torch.empty((r, c), dtype=u8, device=dev), e_row=torch.empty((r, c // 32), dtype=u8, device=dev),
+                        q_col=torch.empty((c, r), dtype=u8, device=dev), e_col=torch.empty((c, r // 32), dtype=u8, device=dev),
+                        s=torch.empty(1, dtype=f32, device=dev))
+        self.qx, self.qdy = qbuf(tokens, k), qbuf(tokens, n)
+
+    def step(self, t):
+        self.moss.weight_autoscale_cast(self.w, self.m, self.v, self.dw, _adamw_args(self.moss, t), self.state,
+                                        wq=self.wq, wq_t=self.wq_t, workspace=self.ws_w)
+
+
+def _moss_linear_fn(torch):
+    class Fn(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, x, layer):
+            moss = layer.moss
+            both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL
+            x = x.contiguous()
+            moss.quant_act_2level(x, both, out=layer.qx, workspace=layer.ws_q)
+            ctx.layer = layer
+            return moss.gemm_fp8_mx(layer.qx["q_row"], layer.qx["e_row"], layer.qx["s"], layer.wq, None, layer.s_w)
+
+        @staticmethod
+        def backward(ctx, dy):
+            layer = ctx.layer
+            moss = layer.moss
+            both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL
+            dy = dy.contiguous()
+            moss.quant_act_2level(dy, both, out=layer.qdy, workspace=layer.ws_q)
+            dx = moss.gemm_fp8_mx(layer.qdy["q_row"], layer.qdy["e_row"], layer.qdy["s"], layer.wq_t, None, layer.s_w)
+            moss.gemm_fp8_mx(layer.qdy["q_col"], layer.qdy["e_col"], layer.qdy["s"], layer.qx["q_col"], layer.qx["e_col"],
+                             layer.qx["s"], out=layer.dw, out_dtype=torch.float32)
+            return dx, None
+    return Fn
+
+
+class _Bf16Linear:
+    def __init__(self, torch, k, n, gen, dev):
+        self.master = torch.nn.Parameter(torch.randn((n, k), generator=gen, device=dev, dtype=torch.float32) * 0.02)
+        self.master.grad = torch.zeros_like(self.master.data)
+        self.w = self.master.data.to(torch.bfloat16)
+        self.dw = self.master.grad
+
+
+def _bf16_linear_fn(torch):
+    class Fn(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, x, layer):
+            ctx.layer = layer
+            ctx.save_for_backward(x)
+            return x @ layer.w.t()
+
+        @staticmethod
+        def backward(ctx, dy):
+            (x,) = ctx.saved_tensors
+            layer = ctx.layer
+            layer.dw.copy_(dy.t() @ x)          # FP32 master gradient from a BF16 GEMM
+            return dy @ layer.w, None
+    return Fn
+
+
+class DecoderBlock:
+    """hidden -> attention -> SwiGLU FFN, pre-norm, as in LLaMA."""
+
+    def __init__(self, moss, torch, arm, batch, seq, hidden, heads, ffn, seed=5):
+        assert arm in ("moss", "bf16") and hidden % heads == 0
+        self.torch, self.moss, self.arm = torch, moss, arm
+        self.batch, self.seq, self.hidden, self.heads, self.ffn = batch, seq, hidden, heads, ffn
+        dev = torch.device("cuda:0")
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(seed)
+        tokens = batch * seq
+        shapes = [("qkv", hidden, 3 * hidden), ("o", hidden, hidden), ("gate", hidden, ffn), ("up", hidden, ffn), ("down", ffn, hidden)]
+        if arm == "moss":
+            self.lin = {n: _MossLinear(moss, torch, tokens, k, nn, gen, dev) for n, k, nn in shapes}
+            self.fn = _moss_linear_fn(torch)
+        else:
+            self.lin = {n: _Bf16Linear(torch, k, nn, gen, dev) for n, k, nn in shapes}
+            self.fn = _bf16_linear_fn(torch)
+            self.opt = torch.optim.AdamW([l.master for l in self.lin.values()], lr=3e-4, betas=(0.9, 0.95), eps=1e-8,
+                                         weight_decay=0.1, fused=True)
+        bf16 = torch.bfloat16
+        self.g1 = torch.ones(hidden, dtype=bf16, device=dev)
+        self.g2 = torch.ones(hidden, dtype=bf16, device=dev)
+        hd = hidden // heads
+        pos = torch.arange(seq, device=dev, dtype=torch.float32)[:, None]
+        inv = 1.0 / (10000.0 ** (torch.arange(0, hd, 2, device=dev, dtype=torch.float32) / hd))[None, :]
+        ang = torch.cat([pos * inv, pos * inv], dim=1)
+        self.cos, self.sin = ang.cos().to(bf16)[None, None], ang.sin().to(bf16)[None, None]
+        self.x = torch.randn((batch, seq, hidden), generator=gen, device=dev, dtype=torch.float32).to(bf16)
+        self.upstream = (torch.randn((batch, seq, hidden), generator=gen, device=dev, dtype=torch.float32) * 1e-3).to(bf16)
+        self.t = 0
+
+    def _rope(self, z):
+        hd = z.shape[-1]
+        rot = self.torch.cat([-z[..., hd // 2:], z[..., :hd // 2]], dim=-1)
+        return z * self.cos + rot * self.sin
+
+    def forward(self, x):
+        torch, F = self.torch, self.torch.nn.functional
+        B, S, H, nh = self.batch, self.seq, self.hidden, self.heads
+        T, hd = B * S, H // nh
+        lin, fn = self.lin, self.fn
+        a = F.rms_norm(x, (H,), self.g1, 1e-5)
+        qkv = fn.apply(a.view(T, H), lin["qkv"]).view(B, S, 3, nh, hd)
+        q, k, v = (qkv[:, :, i].transpose(1, 2) for i in range(3))
+        att = F.scaled_dot_product_attention(self._rope(q), self._rope(k), v, is_causal=True)
+        h = x + fn.apply(att.transpose(1, 2).reshape(T, H), lin["o"]).view(B, S, H)
+        b = F.rms_norm(h, (H,), self.g2, 1e-5).view(T, H)
+        f = F.silu(fn.apply(b, lin["gate"])) * fn.apply(b, lin["up"])
+        return h + fn.apply(f, lin["down"]).view(B, S, H)
+
+    def train_step(self):
+        """forward, backward with the fixed upstream gradient, optimizer step on the five weights"""
+        self.t += 1
+        x = self.x.detach().requires_grad_(True)
+        out = self.forward(x)
+        out.backward(self.upstream)
+        if self.arm == "moss":
+            for l in self.lin.values():
+                l.step(self.t)
+        else:
+            self.opt.step()
+            for l in self.lin.values():
+                l.w.copy_(l.master.data)
+        return out, x.grad
+
+
+def attention_flops(batch, seq, hidden, causal=True):
+    """matmul FLOPs of attention forward + backward (3.5 x forward), halved for the causal mask"""
+    f = 4.0 * batch * seq * seq * hidden
+    return 3.5 * f * (0.5 if causal else 1.0)
+
+
+def linear_flops(batch, seq, hidden, ffn):
+    tokens = batch * seq
+    return 3 * 2.0 * tokens * (hidden * 3 * hidden + hidden * hidden + 3 * hidden * ffn)
+
+
+def sizes_small():
+    return dict(batch=1, seq=64, hidden=256, heads=2, ffn=512)
+
+
+def sizes_7b():
+    return dict(batch=2, seq=4096, hidden=4096, heads=32, ffn=11008)
+
+
+__all__ = ["DecoderBlock", "attention_flops", "linear_flops", "sizes_small", "sizes_7b"]

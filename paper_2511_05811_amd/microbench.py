@@ -5,6 +5,8 @@
                                                          # and the interval sweep of the scaling ablation (App.)
     python -m paper_2511_05811_amd.microbench gemm      # Table "Runtime of quantized FP8 GEMM" (Sec. 4.3): its seven shapes
     python -m paper_2511_05811_amd.microbench snr       # Sec. 3.1 Eq. 3 / SNR table: per-tensor vs two-level microscaling
+    python -m paper_2511_05811_amd.microbench block     # Sec. 4 setting, one decoder block: tokens/s with the linears on the
+                                                         # FP8 path vs BF16 GEMMs (attention, norms, SwiGLU: BF16 torch ops)
     python -m paper_2511_05811_amd.microbench limits    # what the machine allows: GEMM rate and shader clock by operand
                                                          # content (power limit), plain device-copy bandwidth
 
@@ -201,6 +203,37 @@ def snr(moss, torch, small=False):
                     "saturate; moss_ceil rounds it up and never clips"}
 
 
+def block(moss, torch, small=False):
+    """One training step (forward, backward, optimizer) of one LLaMA-7B-shaped decoder block at batch 2 x
+    sequence 4096.  Both arms share the BF16 scaffolding (torch RMSNorm, rotary embedding, causal
+    scaled-dot-product attention, SwiGLU, residuals); only the five linears and their optimizer differ."""
+    import time
+    from . import block as blk
+    sz = blk.sizes_small() if small else blk.sizes_7b()
+    tokens = sz["batch"] * sz["seq"]
+    out = {"table": "block", "sizes": sz, "tokens": tokens, "arms": {}}
+    steps, warm = (3, 2) if small else (8, 3)
+    for arm in ("moss", "bf16"):
+        b = blk.DecoderBlock(moss, torch, arm, **sz)
+        for _ in range(warm):
+            b.train_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            b.train_step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        out["arms"][arm] = {"ms_per_step": round(ms, 3), "tokens_per_s": round(tokens / ms * 1e3, 1)}
+        del b
+        torch.cuda.empty_cache()
+    out["speedup_moss_over_bf16"] = round(out["arms"]["bf16"]["ms_per_step"] / out["arms"]["moss"]["ms_per_step"], 3)
+    out["linear_tflop_per_step"] = round(blk.linear_flops(sz["batch"], sz["seq"], sz["hidden"], sz["ffn"]) / 1e12, 3)
+    out["attention_tflop_per_step"] = round(blk.attention_flops(sz["batch"], sz["seq"], sz["hidden"]) / 1e12, 3)
+    out["note"] = ("bf16 arm: torch matmul (vendor BF16 GEMM) and torch fused AdamW; scaffolding identical in both arms; "
+                   "paper (8 x H800, full 7B model): 1.34x over BF16, context only")
+    return out
+
+
 class _ClockPoller:
     """Samples the shader clock with `rocm-smi --showclocks` (a child process that only reads sysfs)
     while the GPU works."""
@@ -281,7 +314,7 @@ def limits(moss, torch, small=False):
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["scaling", "gemm", "snr", "limits"])
+    ap.add_argument("table", choices=["scaling", "gemm", "snr", "limits", "block"])
     ap.add_argument("--small", action="store_true", help="tiny shapes (used by the tests)")
     a = ap.parse_args(argv)
     import torch
@@ -289,7 +322,7 @@ def main(argv=None):
     if not torch.cuda.is_available():
         print("microbench needs the MI355X", file=sys.stderr)
         return 2
-    res = {"scaling": scaling, "gemm": gemm, "snr": snr, "limits": limits}[a.table](moss, torch, a.small)
+    res = {"scaling": scaling, "gemm": gemm, "snr": snr, "limits": limits, "block": block}[a.table](moss, torch, a.small)
     print(json.dumps(res))
     return 0
 

@@ -40,3 +40,29 @@ def test_limits_table_small():
     res = microbench.limits(moss, torch, small=True)
     assert len(res["gemm_by_operand_content"]) == 3 and all(r["tflops"] > 0 for r in res["gemm_by_operand_content"])
     assert res["device_copy"][0]["gbs_read_plus_write"] > 0
+
+
+def test_decoder_block_arms_agree_on_a_small_block():
+    """The FP8 arm of the decoder-block step stays close to the BF16 arm (same seeds, same scaffolding):
+    outputs, input gradients and weight gradients differ only by quantization noise."""
+    from paper_2511_05811_amd import block as blk
+    sz = blk.sizes_small()
+    a = blk.DecoderBlock(moss, torch, "moss", **sz)
+    b = blk.DecoderBlock(moss, torch, "bf16", **sz)
+    for name in a.lin:      # same initial weights by construction (same generator seed and order)
+        assert torch.allclose(a.lin[name].w, b.lin[name].master.data)
+    oa, ga = a.train_step()
+    ob, gb = b.train_step()
+    torch.cuda.synchronize()
+
+    def rel(x, y):
+        x, y = x.detach().double(), y.detach().double()
+        return float((x - y).norm() / y.norm())
+    assert rel(oa, ob) < 0.02
+    assert rel(ga, gb) < 0.03
+    # dW sums only 64 token products of two FP8-quantized factors here (E4M3 keeps 3 mantissa bits and the
+    # printed round-to-nearest exponent clips group maxima): about 15 % relative noise on this tiny block
+    for name in a.lin:
+        assert rel(a.lin[name].dw, b.lin[name].dw) < 0.25, name
+    res = microbench.block(moss, torch, small=True)
+    assert res["arms"]["moss"]["tokens_per_s"] > 0 and res["arms"]["bf16"]["tokens_per_s"] > 0
