@@ -1,12 +1,16 @@
 // Two-level microscaling quantizer for gfx950 (paper Sec. 3.1, Eq. 1-2).
 //
-// Pass 1 (k_amax_bf16) streams X once and leaves one partial |x| maximum per
-// workgroup in the workspace.  Pass 2 (k_quant_row for row groups alone, k_quant_tile for
-// column groups or both groupings from one fetch of X) folds the
-// partials into the global scale s = amax/448 and then, per group of 32 values,
-// derives the power-of-two local scale from integer / exact FP32 comparisons and
-// emits E4M3 codes of (x * 2^-e) * (1/s).  Magnitudes of finite BF16 values order
-// like their low 15 bits, so every maximum is an integer maximum and is exact.
+// Codes can only be emitted once the maximum of the whole tensor is known (s = amax/448), so
+// every path sees X, agrees on the maximum, and then, per group of 32 values, derives the
+// power-of-two local scale from integer / exact FP32 comparisons and emits the E4M3 codes of
+// (x * 2^-e) * (1/s).  Magnitudes of finite BF16 values order like their low 15 bits, so every
+// maximum is an integer maximum and is exact.
+//
+//  * One launch (k_quant_persist): tensors of up to four 128 x 128 tiles per workgroup of a
+//    co-resident grid stay in registers between the maximum and the codes; X is read once.
+//  * Two launches: k_amax_bf16 leaves one partial maximum per workgroup in the workspace, and
+//    k_quant_row (row groups alone) or k_quant_tile (column groups, or both groupings from one
+//    fetch of X) folds the partials and converts.
 #include <atomic>
 
 #include "moss_internal.h"
