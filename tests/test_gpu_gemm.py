@@ -83,16 +83,19 @@ def test_one_hot_operands_pin_the_lane_and_scale_mapping(oracle):
         assert np.array_equal(out, ref), (m, n, k)
 
 
-def test_fp32_accumulate_and_padded_output(oracle):
-    M, N, K = 70, 52, 192
+@pytest.mark.parametrize("shape,ld", [((70, 52, 192), 64),          # general kernel
+                                      ((600, 1000, 512), 1004),     # large-tile kernel, ld_out % 8 != 0: scalar stores
+                                      ((1024, 776, 640), 784)])     # large-tile kernel, vector stores, ragged N
+def test_fp32_accumulate_and_padded_output(oracle, shape, ld):
+    M, N, K = shape
     rng = np.random.default_rng(9)
     a, b = finite_codes(rng, (M, K)), finite_codes(rng, (N, K))
     ae = rng.integers(115, 128, size=(M, K // 32), dtype=np.uint8)
     ref = oracle.gemm(a, ae, 0.5, b, None, 0.25)
     na, nb = oracle.row_norms(a, ae, 0.5), oracle.row_norms(b, None, 0.25)
-    base = rng.standard_normal((M, 64)).astype(np.float32)
+    base = rng.standard_normal((M, ld)).astype(np.float32)
     buf = to_gpu(base.copy())
-    out = buf[:, :N]                                   # ld_out = 64 > N
+    out = buf[:, :N]                                   # ld_out = ld > N
     sa = to_gpu(np.array([0.5], np.float32)); sb = to_gpu(np.array([0.25], np.float32))
     moss.gemm_fp8_mx(to_gpu(a), to_gpu(ae), sa, to_gpu(b), None, sb, out=out, accumulate=True)
     torch.cuda.synchronize()

@@ -114,10 +114,19 @@ def test_row_stride_larger_than_cols(oracle):
     check_against_oracle(oracle, xb, 0, "strided view", x_dev=x_view)
 
 
-def test_config2_full_size(oracle):
+@pytest.mark.parametrize("flag", [0, CEIL])
+def test_config2_full_size(oracle, flag):
     xb = mi.config2()
     assert xb.shape == (8192, 4096)
-    check_against_oracle(oracle, xb, 0, "config2 full")
+    check_against_oracle(oracle, xb, flag, "config2 full")
+
+
+def test_one_launch_path_on_a_strided_view(oracle):
+    xb_full = mi.heavy_tailed_activation(4128, 2304, seed=49)
+    x_full = bf16_to_gpu(xb_full)
+    x_view = x_full[:, 128:2208]                   # ld = 2304, cols = 2080
+    xb = np.ascontiguousarray(xb_full[:, 128:2208])
+    check_against_oracle(oracle, xb, 0, "one-launch strided view", x_dev=x_view)
 
 
 def test_outputs_are_written_exactly_once_into_caller_buffers(oracle):
