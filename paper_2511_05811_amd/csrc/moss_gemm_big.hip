@@ -113,7 +113,10 @@ struct TileCtx {
     uint32_t a_off[8], b_off[8], ae_off, be_off;
 };
 
-template <bool HAS_BE>
+// MI = 32-row fragments of a per wave: 4 gives the 256 x 256 tile described above, 2 a 128 x 256
+// tile (64 x 128 per wave, half the accumulators) for problems with too few full tiles to fill
+// the machine.  The narrower tile reads 1.5 times the LDS bytes per matrix instruction.
+template <bool HAS_BE, int MI>
 __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, int64_t K,
                                                         const uint8_t *__restrict__ a_q, const uint8_t *__restrict__ a_e,
                                                         const float *__restrict__ a_s,
@@ -122,6 +125,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                                                         void *__restrict__ out, int out_f32, int64_t ld_out, int accumulate,
                                                         int tiles_m, int tiles_n)
 {
+    constexpr int kMT = MI * 64;             // rows of a per tile
+    constexpr int kRowsA = kMT / 4;          // rows of a a wave copies per stage (64 or 32), in kPiecesA pieces of 8
+    constexpr int kPiecesA = kRowsA / 8;
+    constexpr int kPiecesD = kPiecesA + 8;   // copies per stage and wave (a, then b)
+    constexpr int kNM = MI * 4;              // matrix instructions per substep
+    constexpr int kPiecesR = 2 * MI + 8;     // 16-byte fragment reads per substep (a fragments, then b fragments)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
@@ -151,15 +160,16 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         // so that everything derived from them lives in scalar registers)
         const int tm = __builtin_amdgcn_readfirstlane(band * GM + rem % band_rows);
         const int tn = __builtin_amdgcn_readfirstlane(rem / band_rows);
-        c.m0 = (int64_t)tm * kBT;
+        c.m0 = (int64_t)tm * kMT;
         c.n0 = (int64_t)tn * kBT;
-        // per stage a wave copies 64 rows of a and 64 rows of b in eight + eight wave-wide copies
-        // of 8 full rows (8 x 128 B = 1 KiB of LDS) each; rows beyond the matrix repeat the last row
+        // per stage a wave copies kRowsA rows of a and 64 rows of b in wave-wide copies of 8 full rows
+        // (8 x 128 B = 1 KiB of LDS) each; rows beyond the matrix repeat the last row.  In LDS a wave's
+        // rows of a start at row 64 wave whatever kRowsA is (the swizzle only looks at the low row bits).
 #pragma unroll
         for (int s = 0; s < 8; s++) {
             const int r = wave * 64 + s * 8 + (lane >> 3);
             const int ch = (lane & 7) ^ ((r >> 1) & 7);
-            int64_t ra = c.m0 + r, rb = c.n0 + r;
+            int64_t ra = c.m0 + wave * kRowsA + s * 8 + (lane >> 3), rb = c.n0 + r;
             ra = (ra < M ? ra : M - 1) - c.m0;
             rb = (rb < N ? rb : N - 1) - c.n0;
             c.a_off[s] = (uint32_t)(ra * K + ch * 16);
@@ -179,19 +189,19 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         c.be_base = HAS_BE ? b_e + c.n0 * G : nullptr;
     };
 
-    // copy number idx (0..15) of stage P of tile c into the stage slot `par`: 0..7 = 8-row pieces
-    // of a, 8..15 = of b
+    // copy number idx (0 .. kPiecesD-1) of stage P of tile c into the stage slot `par`: first the
+    // 8-row pieces of a, then the eight of b
     auto issue_piece = [&](const TileCtx &c, int P, int par, int idx, bool real = true) {
         // real == false: the copy still runs (keeps the loop free of branches) but lands in a
         // per-wave LDS area that nobody reads
         const uint32_t slot = lds0 + (uint32_t)par * kSlotBytes + (uint32_t)wave * 64 * kStageK;
         const uint32_t dummy = lds0 + kDummyBase + (uint32_t)wave * 1024;
-        if (idx < 8) dma16(c.a_base + (int64_t)P * kStageK, c.a_off[idx], real ? slot + idx * 8 * kStageK : dummy);
-        else dma16(c.b_base + (int64_t)P * kStageK, c.b_off[idx - 8], real ? slot + kBT * kStageK + (idx - 8) * 8 * kStageK : dummy);
+        if (idx < kPiecesA) dma16(c.a_base + (int64_t)P * kStageK, c.a_off[idx], real ? slot + idx * 8 * kStageK : dummy);
+        else dma16(c.b_base + (int64_t)P * kStageK, c.b_off[idx - kPiecesA], real ? slot + kBT * kStageK + (idx - kPiecesA) * 8 * kStageK : dummy);
     };
     auto issue_stage = [&](const TileCtx &c, int P, int par) {
 #pragma unroll
-        for (int idx = 0; idx < 16; idx++) issue_piece(c, P, par, idx);
+        for (int idx = 0; idx < kPiecesD; idx++) issue_piece(c, P, par, idx);
     };
     // First exponent byte of scale block blk: blocks are 16 groups wide; the last one is
     // shifted back so that its 16-byte copy ends exactly at the end of the row.
@@ -205,23 +215,25 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
 
     // ---- LDS -> register fragment plan (substep s of a stage = chunks 4s .. 4s+3 of a row)
     const int sw = (i32 >> 1) & 7;
-    // piece idx (0..15) of the fragments of substep s of the stage in slot `par`: fragment idx/2
-    // (0..3 = a, 4..7 = b), low or high four registers
+    // piece idx (0 .. kPiecesR-1) of the fragments of substep s of the stage in slot `par`: fragment
+    // idx/2 (first the MI of a, then the 4 of b), low or high four registers
     auto read_piece = [&](Frags &f, int par, int s, int idx) {
         const int fr = idx >> 1, half = idx & 1;
+        const int ra = wm * (kMT / 2) + fr * 32;                       // first tile row of the a fragment
         const uint8_t *base = big_smem + par * kSlotBytes +
-                              (fr < 4 ? (wm * 128 + fr * 32 + i32) * kStageK : kBT * kStageK + (wn * 128 + (fr - 4) * 32 + i32) * kStageK);
+                              (fr < MI ? ((ra / kRowsA) * 64 + ra % kRowsA + i32) * kStageK
+                                       : kBT * kStageK + (wn * 128 + (fr - MI) * 32 + i32) * kStageK);
         const uint4 v = *reinterpret_cast<const uint4 *>(base + (((4 * s + 2 * half + h) ^ sw) << 4));
-        v8i &dst = fr < 4 ? f.a[fr] : f.b[fr - 4];
+        v8i &dst = fr < MI ? f.a[fr] : f.b[fr - MI];
         dst[4 * half + 0] = (int)v.x; dst[4 * half + 1] = (int)v.y; dst[4 * half + 2] = (int)v.z; dst[4 * half + 3] = (int)v.w;
     };
     // raw scale dwords of stage P (of a tile whose block 0 sits in scale slot parity sp0)
-    auto read_scales = [&](int (&sa)[4], int (&sb)[4], int P, int sp0) {
+    auto read_scales = [&](int (&sa)[MI], int (&sb)[4], int P, int sp0) {
         const int blk = P >> 2;
         const int dw = 4 * P - scale_block_start(blk);            // byte offset of the stage's dword
         const uint8_t *base = big_smem + kScaleBase + ((sp0 + blk) & 1) * kScaleSlotBytes + dw;
 #pragma unroll
-        for (int i = 0; i < 4; i++) sa[i] = (int)*reinterpret_cast<const uint32_t *>(base + (wm * 128 + i * 32 + i32) * 16);
+        for (int i = 0; i < MI; i++) sa[i] = (int)*reinterpret_cast<const uint32_t *>(base + (wm * (kMT / 2) + i * 32 + i32) * 16);
 #pragma unroll
         for (int j = 0; j < 4; j++)
             sb[j] = HAS_BE ? (int)*reinterpret_cast<const uint32_t *>(base + kBT * 16 + (wn * 128 + j * 32 + i32) * 16)
@@ -234,17 +246,17 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     // registers that matrix instructions in flight still name cost ~190 cycles per stage.  (The
     // shifts are volatile asm so that they stay where they are put.)
     const int sh8 = 8 * h;
-    auto shift_scales = [&](int (&dst_a)[4], int (&dst_b)[4], const int (&sa)[4], const int (&sb)[4]) {
+    auto shift_scales = [&](int (&dst_a)[MI], int (&dst_b)[4], const int (&sa)[MI], const int (&sb)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(dst_a[i]) : "v"(sh8), "v"(sa[i]));
+            if (i < MI) asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(dst_a[i]) : "v"(sh8), "v"(sa[i]));
             asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(dst_b[i]) : "v"(sh8), "v"(sb[i]));
         }
     };
 
-    v16f acc[4][4];
+    v16f acc[MI][4];
     Frags fe, fo;                     // fragments of substep 0 / substep 1
-    int sa0[4], sb0[4], sa1[4], sb1[4], sa_raw[4], sb_raw[4];   // scales of substep 0 / substep 1, raw dwords
+    int sa0[MI], sb0[4], sa1[MI], sb1[4], sa_raw[MI], sb_raw[4];   // scales of substep 0 / substep 1, raw dwords
 
     TileCtx cx;
     make_ctx(0, cx);
@@ -261,15 +273,15 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         const int g0 = ti * T, sp0 = (ti * NB) & 1;      // global stage / scale block numbers of this tile's first
         // Stage 0 and scale block 0 of this tile were issued two stages ago (or by the prologue),
         // stage 1 just now: wait for all but the latter, then fetch the first fragments.
-        wait_vmcnt<16>();
+        wait_vmcnt<kPiecesD>();
         wait_lds_and_barrier();
 #pragma unroll
-        for (int idx = 0; idx < 16; idx++) read_piece(fe, g0 & 1, 0, idx);
+        for (int idx = 0; idx < kPiecesR; idx++) read_piece(fe, g0 & 1, 0, idx);
         read_scales(sa_raw, sb_raw, 0, sp0);
         shift_scales(sa0, sb0, sa_raw, sb_raw);
         asm volatile("s_nop 4" ::: "memory");    // vector ALU write -> scale operand of a matrix instruction
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < MI; i++)
 #pragma unroll
             for (int j = 0; j < 4; j++)
 #pragma unroll
@@ -294,11 +306,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
             const int iP = own ? P + 2 : (issue ? 0 : T - 1);
             // substep 0: multiply K[0,64) while fetching the fragments of K[64,128)
 #pragma unroll
-            for (int idx = 0; idx < 16; idx++) {
+            for (int idx = 0; idx < kNM; idx++) {
                 const int i = idx >> 2, j = idx & 3;
                 mfma_scaled<0>(acc[i][j], fe.b[j], fe.a[i], sb0[j], sa0[i]);
-                read_piece(fo, par, 1, idx);
-                if (idx == 8) shift_scales(sa1, sb1, sa_raw, sb_raw);     // this stage's scales for substep 1
+#pragma unroll
+                for (int p = idx * kPiecesR / kNM; p < (idx + 1) * kPiecesR / kNM; p++) read_piece(fo, par, 1, p);
+                if (idx == kNM / 2) shift_scales(sa1, sb1, sa_raw, sb_raw);     // this stage's scales for substep 1
                 pin();
             }
             if (next) {
@@ -313,12 +326,15 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
             // substep 1: multiply K[64,128), fetch the first fragments of stage P+1, refill the slot
             pin();
 #pragma unroll
-            for (int idx = 0; idx < 16; idx++) {
+            for (int idx = 0; idx < kNM; idx++) {
                 const int i = idx >> 2, j = idx & 3;
                 mfma_scaled<2>(acc[i][j], fo.b[j], fo.a[i], sb1[j], sa1[i]);
-                read_piece(fe, par ^ 1, 0, idx);       // (after the last stage: read and never used)
-                issue_piece(cx, iP, par, idx, issue);
-                if (idx == 8 && next) shift_scales(sa0, sb0, sa_raw, sb_raw);   // the next stage's, for its substep 0
+#pragma unroll
+                for (int p = idx * kPiecesR / kNM; p < (idx + 1) * kPiecesR / kNM; p++)
+                    read_piece(fe, par ^ 1, 0, p);     // (after the last stage: read and never used)
+#pragma unroll
+                for (int p = idx * kPiecesD / kNM; p < (idx + 1) * kPiecesD / kNM; p++) issue_piece(cx, iP, par, p, issue);
+                if (idx == kNM / 2 && next) shift_scales(sa0, sb0, sa_raw, sb_raw);   // the next stage's, for its substep 0
             }
         }
         // (stage 1 of the next tile belongs into the last stage's slot, which the epilogue uses first:
@@ -334,11 +350,11 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         const int epar = (g0 + T - 1) & 1;
         uint8_t *pieceA = big_smem + epar * kSlotBytes + wave * 64 * kStageK;
         uint8_t *pieceB = pieceA + kBT * kStageK;
-        const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;
+        const int64_t mw = m0 + wm * (kMT / 2), nw = n0 + wn * 128;
         if (!out_f32) {
             uint16_t *o = reinterpret_cast<uint16_t *>(out);
 #pragma unroll
-            for (int rnd = 0; rnd < 2; rnd++) {
+            for (int rnd = 0; rnd < MI / 2; rnd++) {
 #pragma unroll
                 for (int ii = 0; ii < 2; ii++) {
                     const int i = 2 * rnd + ii;
@@ -373,7 +389,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         } else {
             float *o = reinterpret_cast<float *>(out);
 #pragma unroll
-            for (int i = 0; i < 4; i++) {       // one 32-row block per round: 32 rows x 512 B, halves in the two pieces
+            for (int i = 0; i < MI; i++) {      // one 32-row block per round: 32 rows x 512 B, halves in the two pieces
 #pragma unroll
                 for (int j = 0; j < 4; j++)
 #pragma unroll
@@ -422,16 +438,27 @@ int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, 
     using namespace moss;
     if (!a_e || K % 128 || K < 512 || K > (1 << 22)) return MOSS_ERR_UNSUPPORTED;
     if ((int64_t)kBT * K >= ((int64_t)1 << 32)) return MOSS_ERR_UNSUPPORTED;
-    const int64_t tiles_m = (M + kBT - 1) / kBT, tiles_n = (N + kBT - 1) / kBT;
+    int cus = moss_internal_cu_count();
+    cus = cus >= 8 ? cus & ~7 : 8;
+    // 256 x 256 tiles when they fill the machine, else 128 x 256 (twice the tiles, each at a somewhat
+    // lower rate).  Time in units of one full tile on all compute units: rounds of full tiles, or rounds
+    // of half tiles at 0.78 each (a half tile takes 0.76 of the time of a full one: 67 us against 88 us
+    // for M = 4096, N = 2048, K = 7168), so the narrow tile pays only where it saves whole rounds.
+    const int64_t tiles_n = (N + kBT - 1) / kBT;
+    const int64_t full = ((M + kBT - 1) / kBT) * tiles_n, half = ((M + kBT / 2 - 1) / (kBT / 2)) * tiles_n;
+    const double t_full = (double)((full + cus - 1) / cus), t_half = 0.78 * (double)((half + cus - 1) / cus);
+    const bool narrow = t_half < t_full;
+    const int64_t tiles_m = narrow ? (M + kBT / 2 - 1) / (kBT / 2) : (M + kBT - 1) / kBT;
     if (tiles_m * tiles_n > 0x7FFFFFF) return MOSS_ERR_UNSUPPORTED;
-    static bool attr_set[2] = {false, false};
-    const int which = b_e ? 1 : 0;
+    using Kern = void (*)(int64_t, int64_t, int64_t, const uint8_t *, const uint8_t *, const float *, const uint8_t *,
+                          const uint8_t *, const float *, void *, int, int64_t, int, int, int);
+    static const Kern kerns[4] = {k_gemm_mx_big<false, 4>, k_gemm_mx_big<true, 4>, k_gemm_mx_big<false, 2>,
+                                  k_gemm_mx_big<true, 2>};
+    static bool attr_set[4] = {false, false, false, false};
+    const int which = (b_e ? 1 : 0) | (narrow ? 2 : 0);
     if (!attr_set[which]) {
-        hipError_t e = b_e ? hipFuncSetAttribute((const void *)k_gemm_mx_big<true>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes)
-                           : hipFuncSetAttribute((const void *)k_gemm_mx_big<false>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
-        if (e != hipSuccess) {
+        if (hipFuncSetAttribute((const void *)kerns[which], hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes) !=
+            hipSuccess) {
             (void)hipGetLastError();
             return MOSS_ERR_UNSUPPORTED;
         }
@@ -440,15 +467,9 @@ int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, 
     // persistent workgroups: one per compute unit (rounded down to a multiple of 8 so that the tiles
     // of a workgroup stay on one XCD), or one per tile if there are fewer tiles
     const int64_t total = tiles_m * tiles_n;
-    int cus = moss_internal_cu_count();
-    cus = cus >= 8 ? cus & ~7 : 8;
     const dim3 grid((unsigned)(total < cus ? total : cus)), block(256);
-    if (b_e)
-        hipLaunchKernelGGL(k_gemm_mx_big<true>, grid, block, kBigLdsBytes, st, M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out,
-                           out_f32, ld_out, accumulate, (int)tiles_m, (int)tiles_n);
-    else
-        hipLaunchKernelGGL(k_gemm_mx_big<false>, grid, block, kBigLdsBytes, st, M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out,
-                           out_f32, ld_out, accumulate, (int)tiles_m, (int)tiles_n);
+    hipLaunchKernelGGL(kerns[which], grid, block, kBigLdsBytes, st, M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out, out_f32,
+                       ld_out, accumulate, (int)tiles_m, (int)tiles_n);
     if (hipGetLastError() != hipSuccess) return MOSS_ERR_HIP;
     return MOSS_OK;
 }
