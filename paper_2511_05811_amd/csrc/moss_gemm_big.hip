@@ -454,8 +454,11 @@ int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, 
                           const uint8_t *, const float *, void *, int, int64_t, int, int, int);
     static const Kern kerns[4] = {k_gemm_mx_big<false, 4>, k_gemm_mx_big<true, 4>, k_gemm_mx_big<false, 2>,
                                   k_gemm_mx_big<true, 2>};
-    static bool attr_set[4] = {false, false, false, false};
+    static bool attr_done[64][4];            // the LDS size attribute is set once per device and kernel
     const int which = (b_e ? 1 : 0) | (narrow ? 2 : 0);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOSS_ERR_HIP;
+    bool(&attr_set)[4] = attr_done[dev];
     if (!attr_set[which]) {
         if (hipFuncSetAttribute((const void *)kerns[which], hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes) !=
             hipSuccess) {

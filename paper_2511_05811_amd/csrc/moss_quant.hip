@@ -683,6 +683,7 @@ PersistFn persist_kernel(bool row, bool col, bool ceil_mode)
 // Workgroups of the one-launch kernel that one compute unit holds at a time, at most 2 (0: do not use it).
 int persist_groups_per_cu(PersistFn fn, int variant)
 {
+    // (a property of the kernel's register and LDS use on gfx950, the same on every device of the process)
     static std::atomic<int> cached[8] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
     int v = cached[variant].load();
     if (v < 0) {
