@@ -23,8 +23,13 @@
 //  * E8M0 scale bytes travel the same way in blocks of 16 bytes (16 groups = K 512) per
 //    row into a small LDS ring; a lane reads one dword per fragment and stage and the
 //    instruction's byte selector picks the group of the substep.
-//  * Epilogue: accumulators times s_a*s_b are staged through LDS (row stride padded by 16
-//    bytes) so that every global store instruction writes whole 256-byte row pieces.
+//  * Epilogue: accumulators times s_a*s_b are staged through the wave's own part of the last
+//    stage slot (16-byte chunks XOR-swizzled by row) so that every global store instruction
+//    writes whole 256-byte row pieces.
+//  * Persistent workgroups, one per compute unit; the first two stages of a workgroup's next
+//    tile are already in flight while it writes out the current one.
+//  * A second instantiation with half the rows of a (128 x 256 tile, 64 x 128 per wave) serves
+//    problems with too few full tiles for the machine.
 //
 // Operand layout of the instruction (measured with one-hot operands): lane (r = lane%32,
 // h = lane/32) supplies for row r the bytes K[16h, 16h+16) in its first four source
@@ -287,13 +292,14 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
 #pragma unroll
                 for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
-        // The stages of this tile.  There is exactly one copy of the 32 matrix instructions in the
-        // kernel (everything optional around them hangs on wave-uniform flags), so the 256
-        // accumulator registers never have to move.  The instruction order is pinned with scheduling
-        // barriers: each matrix instruction is followed by one 16-byte LDS read of the next substep's
-        // fragments and, in substep 1, by one global->LDS copy of the stage after next.  With one wave
-        // per SIMD a burst of memory instructions would block this wave's issue -- and so the matrix
-        // pipe -- until the LDS / texture queues had taken them all.
+        // The stages of this tile.  There is exactly one copy of a stage's matrix instructions in the
+        // kernel (everything optional around them hangs on wave-uniform flags), so the accumulator
+        // registers never have to move.  The instruction order is pinned by the volatile asm statements
+        // and the compiler barriers between them: each matrix instruction is followed by one (narrow
+        // tile: one or two) 16-byte LDS read of the next substep's fragments and, in substep 1, by the
+        // global->LDS copies of the stage after next.  With one wave per SIMD a burst of memory
+        // instructions would block this wave's issue -- and so the matrix pipe -- until the LDS /
+        // texture queues had taken them all.
         const int64_t m0 = cx.m0, n0 = cx.n0;
         for (int P = 0; P < T; P++) {
             const int par = (g0 + P) & 1;            // this stage's slot; the next stage sits in par ^ 1
