@@ -104,3 +104,41 @@ def test_config4_full_size_first_steps(oracle):
     print("[weight parity] config 4 at 4096x11008, 6 steps, re-scaling at step 5", flush=True)
     st = run_parity(oracle, 4096, 11008, 6, seed=4, interval=5, check_every=1)
     assert st.overflow_count == 0 and st.last_rebase == 5
+
+
+def test_config4_full_size_200_steps_never_overflow():
+    """All 200 steps of config 4 at 4096 x 11008 on the GPU (gradients drawn on the device, x20 on the
+    deterministic spike steps): the predicted scale never falls below the exact one, no element is
+    clipped, the by-product amax is the exact maximum of the new weights, and the scale is re-based
+    exactly at the interval (Sec. 3.2, Eq. 6 and its last paragraph)."""
+    rows, cols, interval = 4096, 11008, 50
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4)
+    w = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) * 0.02
+    m = torch.zeros_like(w); v = torch.zeros_like(w)
+    state = moss.new_wscale_state(dev)
+    wq = torch.empty((rows, cols), dtype=torch.uint8, device=dev)
+    wq_t = torch.empty((cols, rows), dtype=torch.uint8, device=dev)
+    moss.weight_autoscale_init(w, state, wq=wq, wq_t=wq_t)
+    rebases = []
+    for t in range(1, 201):
+        g = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) * 1e-3
+        if mi.config4_is_spike_step(t):
+            g *= 20.0
+        hp = mi.adamw_hparams(t, interval=interval)
+        args = moss.AdamWArgs(hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"], hp["one_minus_beta1"],
+                              hp["one_minus_beta2"], hp["bias_corr1"], hp["bias_corr2"], hp["margin"], hp["interval"], t)
+        moss.weight_autoscale_cast(w, m, v, g, args, state, wq=wq, wq_t=wq_t)
+        if t % 10 == 0 or t % interval == 1:
+            st = moss.read_wscale_state(state)
+            assert st.overflow_count == 0, t
+            assert st.s_cur >= st.amax_seen / 448.0 * (1.0 - 1e-6), (t, st.s_cur, st.amax_seen)
+            assert abs(st.amax_seen - float(w.abs().max())) == 0.0
+            if st.last_rebase not in rebases:
+                rebases.append(st.last_rebase)
+    assert rebases == [0, 50, 100, 150, 200]
+    st = moss.read_wscale_state(state)
+    assert st.step == 200 and st.s_cur == np.float32(st.amax_seen) / np.float32(448.0)     # step 200 re-based
+    # transposed codes are the byte transpose of the codes
+    assert torch.equal(wq_t, wq.t().contiguous())
