@@ -271,7 +271,6 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
     issue_stage(cx, 1, 1);
 
     const float scale = (*a_s) * (*b_s);
-    const bool vec_ok = (ld_out % 8 == 0);
 
     for (int ti = 0; ti < n_my_tiles; ti++) {
         const bool has_next = ti + 1 < n_my_tiles;
@@ -381,14 +380,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                     const int rl = 4 * k + (lane >> 4), ii = rl >> 5, rr = rl & 31;
                     const uint4 v = *reinterpret_cast<const uint4 *>((ii ? pieceB : pieceA) + rr * 256 + ((cc ^ (rr & 15)) << 4));
                     const int64_t m = mw + (2 * rnd + ii) * 32 + rr, n = nw + cc * 8;
-                    if (m >= M || n >= N) continue;
-                    uint16_t *dst = o + m * ld_out + n;
-                    if (vec_ok && n + 7 < N) {
-                        *reinterpret_cast<uint4 *>(dst) = v;
-                    } else {
-                        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-                        for (int e = 0; e < 8 && n + e < N; e++) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-                    }
+                    // (N % 8 == 0 and ld_out % 8 == 0 on this path: a piece is inside or outside as a whole)
+                    if (m < M && n < N) *reinterpret_cast<uint4 *>(o + m * ld_out + n) = v;
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged rows consumed before they are overwritten
             }
@@ -413,16 +406,11 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                     const int64_t m = mw + i * 32 + rr, n = nw + l32 * 4;
                     if (m >= M || n >= N) continue;
                     float *dst = o + m * ld_out + n;
-                    if (vec_ok && n + 3 < N) {
-                        if (accumulate) {
-                            const float4 p = *reinterpret_cast<const float4 *>(dst);
-                            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-                        }
-                        *reinterpret_cast<float4 *>(dst) = v;
-                    } else {
-                        const float r[4] = {v.x, v.y, v.z, v.w};
-                        for (int e = 0; e < 4 && n + e < N; e++) dst[e] = accumulate ? dst[e] + r[e] : r[e];
+                    if (accumulate) {
+                        const float4 p = *reinterpret_cast<const float4 *>(dst);
+                        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
                     }
+                    *reinterpret_cast<float4 *>(dst) = v;
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
@@ -443,6 +431,7 @@ int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, 
 {
     using namespace moss;
     if (!a_e || K % 128 || K < 512 || K > (1 << 22)) return MOSS_ERR_UNSUPPORTED;
+    if (N % 8 || ld_out % 8) return MOSS_ERR_UNSUPPORTED;      // the epilogue stores whole 16-byte pieces
     if ((int64_t)kBT * K >= ((int64_t)1 << 32)) return MOSS_ERR_UNSUPPORTED;
     int cus = moss_internal_cu_count();
     cus = cus >= 8 ? cus & ~7 : 8;
