@@ -6,7 +6,8 @@
  *
  * Conventions for every entry point
  *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
- *    allocates nothing and keeps no hidden state besides cached device properties.
+ *    allocates nothing and keeps no hidden state besides cached device properties
+ *    and the one process-wide setting of moss_quant_set_poll_limit.
  *    Pointers to `moss_adamw_args` are HOST pointers (read during the call).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *    work is enqueued asynchronously on it; nothing synchronizes with the host.
@@ -62,7 +63,8 @@ int moss_device_cu_count(void);
  *            never saturates a code).  Stored as the E8M0 byte e_i + 127; an
  *            all-zero group stores byte 0.
  *   codes    E4M3 (max 448) of  y = fl32(x * fl32(1/s)) * 2^(-e_i), rounded to
- *            nearest even, saturated to +-448, sign kept.
+ *            nearest even, saturated to +-448, sign kept (fl32(1/s) is capped at
+ *            FLT_MAX, so a zero input has code zero whatever the scale).
  *
  * MOSS_Q_ROW: groups run along the columns (the inner dimension of Y = X W^T and
  *             of dX = dY W): q_row [rows x cols], e_row [rows x cols/32].
