@@ -465,7 +465,13 @@ int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, 
     // persistent workgroups: one per compute unit (rounded down to a multiple of 8 so that the tiles
     // of a workgroup stay on one XCD), or one per tile if there are fewer tiles
     const int64_t total = tiles_m * tiles_n;
-    const dim3 grid((unsigned)(total < cus ? total : cus)), block(256);
+    // No more workgroups than the rounds need: 1376 tiles take 6 rounds on 256 compute units and on 232
+    // alike, and under the power limit the idle units' share goes into the clock of the busy ones.
+    const int64_t rounds = (total + cus - 1) / cus;
+    int64_t wgs = (total + rounds - 1) / rounds;
+    wgs = (wgs + 7) & ~(int64_t)7;
+    if (wgs > cus) wgs = cus;
+    const dim3 grid((unsigned)(total < cus ? total : wgs)), block(256);
     hipLaunchKernelGGL(kerns[which], grid, block, kBigLdsBytes, st, M, N, K, a_q, a_e, a_s, b_q, b_e, b_s, out, out_f32,
                        ld_out, accumulate, (int)tiles_m, (int)tiles_n);
     if (hipGetLastError() != hipSuccess) return MOSS_ERR_HIP;
