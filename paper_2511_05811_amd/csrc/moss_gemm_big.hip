@@ -194,19 +194,13 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         c.be_base = HAS_BE ? b_e + c.n0 * G : nullptr;
     };
 
-    // copy number idx (0 .. kPiecesD-1) of stage P of tile c into the stage slot `par`: first the
-    // 8-row pieces of a, then the eight of b
-    auto issue_piece = [&](const TileCtx &c, int P, int par, int idx, bool real = true) {
-        // real == false: the copy still runs (keeps the loop free of branches) but lands in a
-        // per-wave LDS area that nobody reads
-        const uint32_t slot = lds0 + (uint32_t)par * kSlotBytes + (uint32_t)wave * 64 * kStageK;
-        const uint32_t dummy = lds0 + kDummyBase + (uint32_t)wave * 1024;
-        if (idx < kPiecesA) dma16(c.a_base + (int64_t)P * kStageK, c.a_off[idx], real ? slot + idx * 8 * kStageK : dummy);
-        else dma16(c.b_base + (int64_t)P * kStageK, c.b_off[idx - kPiecesA], real ? slot + kBT * kStageK + (idx - kPiecesA) * 8 * kStageK : dummy);
-    };
+    // all copies of stage P of tile c into the stage slot `par`: first the 8-row pieces of a, then the eight of b
     auto issue_stage = [&](const TileCtx &c, int P, int par) {
+        const uint32_t slot = lds0 + (uint32_t)par * kSlotBytes + (uint32_t)wave * 64 * kStageK;
 #pragma unroll
-        for (int idx = 0; idx < kPiecesD; idx++) issue_piece(c, P, par, idx);
+        for (int idx = 0; idx < kPiecesA; idx++) dma16(c.a_base + (int64_t)P * kStageK, c.a_off[idx], slot + idx * 8 * kStageK);
+#pragma unroll
+        for (int idx = 0; idx < 8; idx++) dma16(c.b_base + (int64_t)P * kStageK, c.b_off[idx], slot + kBT * kStageK + idx * 8 * kStageK);
     };
     // First exponent byte of scale block blk: blocks are 16 groups wide; the last one is
     // shifted back so that its 16-byte copy ends exactly at the end of the row.
@@ -232,11 +226,15 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         v8i &dst = fr < MI ? f.a[fr] : f.b[fr - MI];
         dst[4 * half + 0] = (int)v.x; dst[4 * half + 1] = (int)v.y; dst[4 * half + 2] = (int)v.z; dst[4 * half + 3] = (int)v.w;
     };
-    // raw scale dwords of stage P (of a tile whose block 0 sits in scale slot parity sp0)
-    auto read_scales = [&](int (&sa)[MI], int (&sb)[4], int P, int sp0) {
+    // LDS byte offset (from the scale area) of the dword that holds the four exponent bytes of stage P, for a
+    // tile whose scale block 0 sits in scale slot parity sp0
+    auto scale_dword_offset = [&](int P, int sp0) {
         const int blk = P >> 2;
-        const int dw = 4 * P - scale_block_start(blk);            // byte offset of the stage's dword
-        const uint8_t *base = big_smem + kScaleBase + ((sp0 + blk) & 1) * kScaleSlotBytes + dw;
+        return (uint32_t)(((sp0 + blk) & 1) * kScaleSlotBytes + 4 * P - scale_block_start(blk));
+    };
+    // raw scale dwords of the stage at that offset
+    auto read_scales = [&](int (&sa)[MI], int (&sb)[4], uint32_t off) {
+        const uint8_t *base = big_smem + kScaleBase + off;
 #pragma unroll
         for (int i = 0; i < MI; i++) sa[i] = (int)*reinterpret_cast<const uint32_t *>(base + (wm * (kMT / 2) + i * 32 + i32) * 16);
 #pragma unroll
@@ -281,7 +279,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         wait_lds_and_barrier();
 #pragma unroll
         for (int idx = 0; idx < kPiecesR; idx++) read_piece(fe, g0 & 1, 0, idx);
-        read_scales(sa_raw, sb_raw, 0, sp0);
+        read_scales(sa_raw, sb_raw, scale_dword_offset(0, sp0));
         shift_scales(sa0, sb0, sa_raw, sb_raw);
         asm volatile("s_nop 4" ::: "memory");    // vector ALU write -> scale operand of a matrix instruction
 #pragma unroll
@@ -302,13 +300,18 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         const int64_t m0 = cx.m0, n0 = cx.n0;
         for (int P = 0; P < T; P++) {
             const int par = (g0 + P) & 1;            // this stage's slot; the next stage sits in par ^ 1
-            const bool next = P + 1 < T;             // the epilogue, not this loop, hands over to the next tile
-            // what goes into slot `par` once it is free: stage P+2 of this tile, or stage 0 of the next
-            const bool own = P + 2 < T;
-            const bool issue = own || (P + 2 == T && has_next);
-            // (when there is nothing to issue -- the last stage, and the one before it for the last
-            // tile -- the copies are kept, aimed at stage T-1 again and at the unread LDS area)
-            const int iP = own ? P + 2 : (issue ? 0 : T - 1);
+            // Everything the middle of the stage and substep 1 need to know is worked out in the shadow of
+            // the first matrix instructions of substep 0 (the empty asm statements fence the scalar code in
+            // between them: with one wave per SIMD whatever runs between two substeps leaves the matrix
+            // pipe idle):
+            //   next  : there is a stage P+1 in this tile (the epilogue, not this loop, hands over to the next tile)
+            //   own   : slot `par` is refilled with stage P+2 of this tile
+            //   issue : ... or with stage 0 of the next tile; when there is nothing to refill (the last stage, and
+            //           the one before it for the last tile) the copies still run, aimed at stage T-1 again and at
+            //           an LDS area nobody reads, which keeps the loop free of branches
+            int fl = 0, iP = 0;
+            uint32_t sc_off = 0, dst_a = 0, dst_b = 0, dstep = 0;
+            const uint8_t *a_src = nullptr, *b_src = nullptr;
             // substep 0: multiply K[0,64) while fetching the fragments of K[64,128)
 #pragma unroll
             for (int idx = 0; idx < kNM; idx++) {
@@ -316,20 +319,43 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                 mfma_scaled<0>(acc[i][j], fe.b[j], fe.a[i], sb0[j], sa0[i]);
 #pragma unroll
                 for (int p = idx * kPiecesR / kNM; p < (idx + 1) * kPiecesR / kNM; p++) read_piece(fo, par, 1, p);
+                if (idx == 0) {
+                    int Pl = P;
+                    asm volatile("" : "+s"(Pl));
+                    const bool next = Pl + 1 < T, own = Pl + 2 < T, issue = own || (Pl + 2 == T && has_next);
+                    iP = own ? Pl + 2 : (issue ? 0 : T - 1);
+                    fl = T - Pl < 3 ? T - Pl : 3;                      // stages left in this tile, capped: 1, 2 or 3
+                    sc_off = scale_dword_offset(Pl + 1, sp0);
+                    a_src = cx.a_base + (int64_t)iP * kStageK;
+                    b_src = cx.b_base + (int64_t)iP * kStageK;
+                    const uint32_t slot = lds0 + (uint32_t)par * kSlotBytes + (uint32_t)wave * 64 * kStageK;
+                    const uint32_t dummy = lds0 + kDummyBase + (uint32_t)wave * 1024;
+                    dst_a = issue ? slot : dummy;
+                    dst_b = issue ? slot + kBT * kStageK : dummy;
+                    dstep = issue ? 8 * kStageK : 0;
+                }
+                if (idx == 3)
+                    asm volatile("" : "+s"(fl), "+s"(iP), "+s"(sc_off), "+s"(a_src), "+s"(b_src), "+s"(dst_a), "+s"(dst_b), "+s"(dstep));
                 if (idx == kNM / 2) shift_scales(sa1, sb1, sa_raw, sb_raw);     // this stage's scales for substep 1
                 pin();
             }
+            const bool next = fl >= 2, own = fl == 3, issue = own || (next && has_next);
             if (next) {
                 wait_vmcnt<0>();          // this wave's part of stage P+1 (and its scales) has landed
                 wait_lds_and_barrier();   // ... and everyone is done reading this stage's slot
-                read_scales(sa_raw, sb_raw, P + 1, sp0);
+                read_scales(sa_raw, sb_raw, sc_off);
             }
             if (issue) {
-                if (!own) make_ctx(ti + 1, cx);      // from here on cx describes the next tile
+                if (!own) {               // from here on cx describes the next tile
+                    make_ctx(ti + 1, cx);
+                    a_src = cx.a_base;
+                    b_src = cx.b_base;
+                }
                 if ((iP & 3) == 0) issue_scales(cx, iP >> 2, own ? (sp0 + (iP >> 2)) & 1 : (sp0 + NB) & 1);
             }
             // substep 1: multiply K[64,128), fetch the first fragments of stage P+1, refill the slot
             pin();
+            uint32_t cur = dst_a;
 #pragma unroll
             for (int idx = 0; idx < kNM; idx++) {
                 const int i = idx >> 2, j = idx & 3;
@@ -338,7 +364,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                 for (int p = idx * kPiecesR / kNM; p < (idx + 1) * kPiecesR / kNM; p++)
                     read_piece(fe, par ^ 1, 0, p);     // (after the last stage: read and never used)
 #pragma unroll
-                for (int p = idx * kPiecesD / kNM; p < (idx + 1) * kPiecesD / kNM; p++) issue_piece(cx, iP, par, p, issue);
+                for (int p = idx * kPiecesD / kNM; p < (idx + 1) * kPiecesD / kNM; p++) {
+                    if (p == kPiecesA) cur = dst_b;
+                    if (p < kPiecesA) dma16(a_src, cx.a_off[p], cur);
+                    else dma16(b_src, cx.b_off[p - kPiecesA], cur);
+                    cur += dstep;
+                }
                 if (idx == kNM / 2 && next) shift_scales(sa0, sb0, sa_raw, sb_raw);   // the next stage's, for its substep 0
             }
         }
