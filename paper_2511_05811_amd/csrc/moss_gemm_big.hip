@@ -309,7 +309,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
             //   issue : ... or with stage 0 of the next tile; when there is nothing to refill (the last stage, and
             //           the one before it for the last tile) the copies still run, aimed at stage T-1 again and at
             //           an LDS area nobody reads, which keeps the loop free of branches
-            int fl = 0, iP = 0;
+            int fl = 0, iP = 0, Pl = 0;
             uint32_t sc_off = 0, dst_a = 0, dst_b = 0, dstep = 0;
             const uint8_t *a_src = nullptr, *b_src = nullptr;
             // substep 0: multiply K[0,64) while fetching the fragments of K[64,128)
@@ -319,23 +319,33 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                 mfma_scaled<0>(acc[i][j], fe.b[j], fe.a[i], sb0[j], sa0[i]);
 #pragma unroll
                 for (int p = idx * kPiecesR / kNM; p < (idx + 1) * kPiecesR / kNM; p++) read_piece(fo, par, 1, p);
+                // (a chain of fenced pieces, one behind each of the first matrix instructions)
                 if (idx == 0) {
-                    int Pl = P;
+                    Pl = P;
                     asm volatile("" : "+s"(Pl));
-                    const bool next = Pl + 1 < T, own = Pl + 2 < T, issue = own || (Pl + 2 == T && has_next);
+                    const bool own = Pl + 2 < T, issue = own || (Pl + 2 == T && has_next);
                     iP = own ? Pl + 2 : (issue ? 0 : T - 1);
                     fl = T - Pl < 3 ? T - Pl : 3;                      // stages left in this tile, capped: 1, 2 or 3
+                }
+                if (idx == 1) {
+                    asm volatile("" : "+s"(fl), "+s"(iP), "+s"(Pl));
                     sc_off = scale_dword_offset(Pl + 1, sp0);
+                }
+                if (idx == 2) {
+                    asm volatile("" : "+s"(sc_off), "+s"(iP));
                     a_src = cx.a_base + (int64_t)iP * kStageK;
                     b_src = cx.b_base + (int64_t)iP * kStageK;
+                }
+                if (idx == 3) {
+                    asm volatile("" : "+s"(a_src), "+s"(b_src), "+s"(fl));
+                    const bool issue = fl == 3 || (fl == 2 && has_next);
                     const uint32_t slot = lds0 + (uint32_t)par * kSlotBytes + (uint32_t)wave * 64 * kStageK;
                     const uint32_t dummy = lds0 + kDummyBase + (uint32_t)wave * 1024;
                     dst_a = issue ? slot : dummy;
                     dst_b = issue ? slot + kBT * kStageK : dummy;
                     dstep = issue ? 8 * kStageK : 0;
                 }
-                if (idx == 3)
-                    asm volatile("" : "+s"(fl), "+s"(iP), "+s"(sc_off), "+s"(a_src), "+s"(b_src), "+s"(dst_a), "+s"(dst_b), "+s"(dstep));
+                if (idx == 4) asm volatile("" : "+s"(dst_a), "+s"(dst_b), "+s"(dstep));
                 if (idx == kNM / 2) shift_scales(sa1, sb1, sa_raw, sb_raw);     // this stage's scales for substep 1
                 pin();
             }
