@@ -15,11 +15,16 @@
 //    substep are read from LDS, one 16-byte read after each of the 16 matrix instructions
 //    of the current one.
 //  * The loads of stage P+2 are issued during substep 1 of stage P (their slot is free from
-//    then on), one copy after each matrix instruction, and have to land by the end of
-//    substep 0 of stage P+1: one to two substeps (1024 matrix-core cycles each) of latency
+//    then on), one copy after each matrix instruction, and have to land by the middle of
+//    substep 1 of stage P+1: two to three substeps (1024 matrix-core cycles each) of latency
 //    hiding with 64 KiB in flight.
-//  * One barrier per stage, at the end of substep 0; before it every wave waits for its
-//    own outstanding loads (stage P+1) and LDS reads.
+//  * Two barriers per stage.  The first, at the end of substep 0, only says that every wave
+//    has read the stage's last fragments, so the slot may be refilled.  The second sits in the
+//    middle of substep 1: before it every wave waits for its own copies of stage P+1, behind it
+//    the first fragments of stage P+1 are read, two 16-byte reads per matrix instruction.
+//    (With a single barrier at the end of substep 0 that also waited for the copies, they had
+//    one to two substeps; an L2 miss takes longer, and inside a training step, where every
+//    GEMM starts on cold operands, the later wait is worth 5 % of the GEMM time.)
 //  * E8M0 scale bytes travel the same way in blocks of 16 bytes (16 groups = K 512) per
 //    row into a small LDS ring; a lane reads one dword per fragment and stage and the
 //    instruction's byte selector picks the group of the substep.
@@ -292,9 +297,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
         // The stages of this tile.  There is exactly one copy of a stage's matrix instructions in the
         // kernel (everything optional around them hangs on wave-uniform flags), so the accumulator
         // registers never have to move.  The instruction order is pinned by the volatile asm statements
-        // and the compiler barriers between them: each matrix instruction is followed by one (narrow
-        // tile: one or two) 16-byte LDS read of the next substep's fragments and, in substep 1, by the
-        // global->LDS copies of the stage after next.  With one wave per SIMD a burst of memory
+        // and the compiler barriers between them: in substep 0 each matrix instruction is followed by one
+        // (narrow tile: one or two) 16-byte LDS read of substep 1's fragments, in substep 1 by the global->LDS
+        // copies of the stage after next and, in its second half, by the reads of the next stage's first fragments.  With one wave per SIMD a burst of memory
         // instructions would block this wave's issue -- and so the matrix pipe -- until the LDS /
         // texture queues had taken them all.
         const int64_t m0 = cx.m0, n0 = cx.n0;
@@ -350,29 +355,34 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                 pin();
             }
             const bool next = fl >= 2, own = fl == 3, issue = own || (next && has_next);
-            if (next) {
-                wait_vmcnt<0>();          // this wave's part of stage P+1 (and its scales) has landed
-                wait_lds_and_barrier();   // ... and everyone is done reading this stage's slot
-                read_scales(sa_raw, sb_raw, sc_off);
+            if (next) wait_lds_and_barrier();    // everyone is done reading this stage's slot: it may be refilled
+            if (issue && !own) {                 // from here on cx describes the next tile
+                make_ctx(ti + 1, cx);
+                a_src = cx.a_base;
+                b_src = cx.b_base;
             }
-            if (issue) {
-                if (!own) {               // from here on cx describes the next tile
-                    make_ctx(ti + 1, cx);
-                    a_src = cx.a_base;
-                    b_src = cx.b_base;
-                }
-                if ((iP & 3) == 0) issue_scales(cx, iP >> 2, own ? (sp0 + (iP >> 2)) & 1 : (sp0 + NB) & 1);
-            }
-            // substep 1: multiply K[64,128), fetch the first fragments of stage P+1, refill the slot
+            // substep 1: multiply K[64,128) and refill the slot.  Stage P+1 is only waited for in the middle of
+            // the substep (its copies have had a stage and a quarter by then); the first fragments of stage
+            // P+1 are fetched behind that second barrier, two reads per matrix instruction.
             pin();
             uint32_t cur = dst_a;
+            constexpr int kBB = kNM / 2;                         // the matrix instruction the second barrier follows
+            constexpr int kBefore = kBB * kPiecesD / kNM;        // copies of this substep issued before it
 #pragma unroll
             for (int idx = 0; idx < kNM; idx++) {
                 const int i = idx >> 2, j = idx & 3;
                 mfma_scaled<2>(acc[i][j], fo.b[j], fo.a[i], sb1[j], sa1[i]);
+                if (idx == kBB && next) {
+                    wait_vmcnt<kBefore>();    // this wave's part of stage P+1 (and its scales) has landed
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    read_scales(sa_raw, sb_raw, sc_off);
+                }
+                if (idx >= kBB) {
 #pragma unroll
-                for (int p = idx * kPiecesR / kNM; p < (idx + 1) * kPiecesR / kNM; p++)
-                    read_piece(fe, par ^ 1, 0, p);     // (after the last stage: read and never used)
+                    for (int p = (idx - kBB) * kPiecesR / (kNM - kBB); p < (idx - kBB + 1) * kPiecesR / (kNM - kBB); p++)
+                        read_piece(fe, par ^ 1, 0, p);     // (after the last stage: read and never used)
+                }
 #pragma unroll
                 for (int p = idx * kPiecesD / kNM; p < (idx + 1) * kPiecesD / kNM; p++) {
                     if (p == kPiecesA) cur = dst_b;
@@ -380,8 +390,10 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                     else dma16(b_src, cx.b_off[p - kPiecesA], cur);
                     cur += dstep;
                 }
-                if (idx == kNM / 2 && next) shift_scales(sa0, sb0, sa_raw, sb_raw);   // the next stage's, for its substep 0
+                if (idx == kBB + (kNM - kBB) / 2 && next) shift_scales(sa0, sb0, sa_raw, sb_raw);   // the next stage's, for its substep 0
             }
+            // the next scale block, behind this substep's copies (the wait above counts back from the newest copy)
+            if (issue && (iP & 3) == 0) issue_scales(cx, iP >> 2, own ? (sp0 + (iP >> 2)) & 1 : (sp0 + NB) & 1);
         }
         // (stage 1 of the next tile belongs into the last stage's slot, which the epilogue uses first:
         // it is issued after the epilogue)
