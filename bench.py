@@ -30,7 +30,7 @@ QUANT_BYTES_PER_ELEM_BOTH = 4.0625   # read 2 B, write 2 x (1 + 1/32) B
 WEIGHT_BYTES_PER_ELEM = 30.0         # W, m, v read+write (24) + FP32 grad (4) + codes (1) + transposed codes (1)
 # Mean bytes per GEMM launch crossing the L2 boundary (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 from two
 # rocprofv3 --pmc runs of this script; summary and scale factors in profiles/bench_config3_hbm_traffic.md).
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 6.91e8
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 6.98e8
 
 
 def log(*a):
