@@ -11,9 +11,9 @@
 //    kernel needs 32 B/clk/CU at full matrix-core rate.)
 //  * Two LDS stage slots of 64 KiB (256 rows of a, 256 rows of b) filled by direct
 //    global->LDS loads that never touch registers.  A stage is multiplied in two substeps
-//    of K = 64; fragments are double buffered in registers: the fragments of the next
-//    substep are read from LDS, one 16-byte read after each of the 16 matrix instructions
-//    of the current one.
+//    of K = 64; fragments are double buffered in registers: substep 1's are read from LDS
+//    behind the 16 matrix instructions of substep 0, one 16-byte read each, the next stage's
+//    first ones behind the second half of substep 1's (see the barriers below).
 //  * The loads of stage P+2 are issued during substep 1 of stage P (their slot is free from
 //    then on), one copy after each matrix instruction, and have to land by the middle of
 //    substep 1 of stage P+1: two to three substeps (1024 matrix-core cycles each) of latency
