@@ -67,6 +67,26 @@ def test_random_codes_all_tile_edges(oracle, shape, exps):
     assert_close(bf16_out_to_f64(out), ref, na, nb, True, f"{shape} {exps} bf16")
 
 
+@pytest.mark.parametrize("K", [512, 640])
+def test_more_tiles_than_compute_units_full_compare(oracle, K):
+    """17 x 16 = 272 tiles of 256 x 256 on 256 compute units: every workgroup of the persistent grid
+    hands over from one tile to the next (with K = 512 after the shortest possible main loop of four
+    stages, with K = 640 after an odd number of stages, so the LDS slots swap roles between tiles),
+    and the grid is trimmed to the 136 workgroups two rounds need.  Every output is compared."""
+    M, N = 4352 - 3, 4096
+    rng = np.random.default_rng(K)
+    a, b = finite_codes(rng, (M, K)), finite_codes(rng, (N, K))
+    ae = rng.integers(110, 128, size=(M, K // 32), dtype=np.uint8)
+    be = rng.integers(110, 128, size=(N, K // 32), dtype=np.uint8) if K == 640 else None
+    a_s, b_s = np.float32(0.5), np.float32(0.25)
+    ref = oracle.gemm(a, ae, a_s, b, be, b_s)
+    na, nb = oracle.row_norms(a, ae, a_s), oracle.row_norms(b, be, b_s)
+    out = gpu_gemm(a, ae, a_s, b, be, b_s, out_dtype=torch.float32)
+    assert_close(out.cpu().numpy().astype(np.float64), ref, na, nb, False, f"272 tiles K={K} f32")
+    out = gpu_gemm(a, ae, a_s, b, be, b_s, out_dtype=torch.bfloat16)
+    assert_close(bf16_out_to_f64(out), ref, na, nb, True, f"272 tiles K={K} bf16")
+
+
 def test_one_hot_operands_pin_the_lane_and_scale_mapping(oracle):
     # a single nonzero code in a and in b at the same k: exactly one output is nonzero and
     # equals the product of the two decoded values and their two level-2 scales
