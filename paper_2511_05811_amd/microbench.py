@@ -196,11 +196,26 @@ def snr(moss, torch, small=False):
     out["per_tensor"] = round(snr_db(deq), 2)
     nonout = torch.ones(cols, dtype=torch.bool, device=dev); nonout[idx] = False
     out["per_tensor_non_outlier_channels"] = round(float(10.0 * torch.log10((xd * xd)[:, nonout].sum() / ((xd - deq) ** 2)[:, nonout].sum())), 2)
+    # comparator, computed here with torch operations (not a library path): one FP32 scale per group of 128
+    # along the row, codes by rounding to the nearest E4M3 value
+    g128 = 128
+    xg = xd.view(rows, cols // g128, g128)
+    sg = (xg.abs().amax(dim=2, keepdim=True).float() / 448.0).double()
+    sg = torch.where(sg == 0, torch.ones_like(sg), sg)
+    y = (xg / sg).clamp(-448.0, 448.0)
+    vals = table[:127]                                           # 0 ... 448, ascending
+    near = vals[torch.bucketize(y.abs(), (vals[1:] + vals[:-1]) / 2.0)]
+    deq = (torch.sign(y) * near * sg).view(rows, cols)
+    out["per_group_128_fp32_scales"] = round(snr_db(deq), 2)
+    out["per_group_128_fp32_scales_non_outlier_channels"] = round(
+        float(10.0 * torch.log10((xd * xd)[:, nonout].sum() / ((xd - deq) ** 2)[:, nonout].sum())), 2)
     return {"table": "snr", "unit": "dB", "shape": [rows, cols], "snr": out,
             "note": "paper (activations of a trained 7B model): two-level 3.0-3.4 dB above per-group-128, 9.2-9.4 dB above per-tensor; "
                     "synthetic heavy-tailed tensors stand in, so only the ordering is comparable.  moss_nearest rounds the local exponent "
                     "to the closest power of two as Eq. 2 prints it, which lets a group maximum exceed 448 by up to sqrt(2) and "
-                    "saturate; moss_ceil rounds it up and never clips"}
+                    "saturate; moss_ceil rounds it up and never clips.  per_group_128_fp32_scales is a comparator computed with torch "
+                    "operations; its whole-tensor figure is flattered by the outlier channels, which carry most of the power and, being "
+                    "their groups' maxima, are represented exactly: compare the non-outlier columns"}
 
 
 def block(moss, torch, small=False):
