@@ -127,9 +127,30 @@ static int local_exponent(double amax_i, double amax, int mode)
  *             (q[cols][rows], e[cols][rows/32]).
  * exp_mode 0 nearest (Eq. 2), 1 ceil.
  * The global scale s is per tensor and does not depend on axis.        */
+static int quant_with_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, int axis, int exp_mode,
+                          double given_max, uint8_t *q, uint8_t *e, float *s_global);
+
 int moss_oracle_quant_act_2level(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
                                  int axis, int exp_mode,
                                  uint8_t *q, uint8_t *e, float *s_global)
+{
+    return quant_with_max(x, rows, cols, ld, axis, exp_mode, -1.0, q, e, s_global);
+}
+
+/* The same with the tensor maximum of Eq. 1 handed in by whoever produced X (BF16 magnitude bits)
+ * instead of being searched for: it has to be at least max|X|; with exactly max|X| the result is that
+ * of moss_oracle_quant_act_2level.                                                                  */
+int moss_oracle_quant_act_2level_given_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
+                                           int axis, int exp_mode, uint16_t max_bf16_bits,
+                                           uint8_t *q, uint8_t *e, float *s_global)
+{
+    double given = bf16_to_double((uint16_t)(max_bf16_bits & 0x7FFF));
+    if (!isfinite(given)) return MOSS_O_NONFINITE;
+    return quant_with_max(x, rows, cols, ld, axis, exp_mode, given, q, e, s_global);
+}
+
+static int quant_with_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, int axis, int exp_mode,
+                          double given_max, uint8_t *q, uint8_t *e, float *s_global)
 {
     if (!x || !q || !e || !s_global) return MOSS_O_BAD_ARG;
     if (rows <= 0 || cols <= 0 || ld < cols) return MOSS_O_BAD_ARG;
@@ -144,6 +165,10 @@ int moss_oracle_quant_act_2level(const uint16_t *x, int64_t rows, int64_t cols, 
             if (!isfinite(v)) return MOSS_O_NONFINITE;
             if (v > amax) amax = v;
         }
+    if (given_max >= 0.0) {
+        if (given_max < amax) return MOSS_O_BAD_ARG;    /* not a bound of |X| */
+        amax = given_max;
+    }
     float s = 1.0f;                       /* all-zero tensor: s = 1 */
     if (amax > 0.0) s = (float)amax / 448.0f;   /* one IEEE single division */
     float inv_s = 1.0f / s;               /* one IEEE single division */
@@ -403,6 +428,39 @@ int moss_oracle_row_norms(int64_t R, int64_t K, const uint8_t *q, const uint8_t 
 
 /* Quantization SNR in dB (Sec. 3.1, Eq. 3 of that section):
  * 10 log10( sum x^2 / sum (dq - x)^2 ).                                  */
+/* ------------------------------------------------------------------ */
+/* The producer on the input side of the down projection (the paper leaves the non-linear
+ * layers in BF16, Sec. 4.1): SwiGLU of a LLaMA feed-forward block,
+ *      h = silu(g) * u,   silu(g) = g / (1 + exp(-g)),
+ * from BF16 gate and up projections, in double.  Backward for an upstream gradient dh:
+ *      d_up = dh * silu(g),   d_gate = dh * u * sig(g) * (1 + g * (1 - sig(g))),   sig(g) = 1 / (1 + exp(-g)).
+ * The outputs are the exact doubles: rounding them to BF16 (and taking the maximum of the rounded
+ * magnitudes that the quantizer wants) is left to the caller, who knows which rounding he compares with. */
+int moss_oracle_swiglu(const uint16_t *gate, const uint16_t *up, int64_t n, double *h)
+{
+    if (!gate || !up || !h || n < 0) return MOSS_O_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; i++) {
+        double g = bf16_to_double(gate[i]), u = bf16_to_double(up[i]);
+        h[i] = g / (1.0 + exp(-g)) * u;
+    }
+    return MOSS_O_OK;
+}
+
+int moss_oracle_swiglu_backward(const uint16_t *gate, const uint16_t *up, const uint16_t *dh, int64_t n,
+                                double *d_gate, double *d_up)
+{
+    if (!gate || !up || !dh || !d_gate || !d_up || n < 0) return MOSS_O_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; i++) {
+        double g = bf16_to_double(gate[i]), u = bf16_to_double(up[i]), d = bf16_to_double(dh[i]);
+        double sig = 1.0 / (1.0 + exp(-g));
+        d_up[i] = d * (g * sig);
+        d_gate[i] = d * u * (sig * (1.0 + g * (1.0 - sig)));
+    }
+    return MOSS_O_OK;
+}
+
 double moss_oracle_snr_db(const double *x, const double *dq, int64_t n)
 {
     double ps = 0.0, pn = 0.0;

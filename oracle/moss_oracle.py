@@ -63,6 +63,10 @@ def lib():
         L.moss_oracle_snr_db.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
         L.moss_oracle_quant_act_2level.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                                    C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.moss_oracle_quant_act_2level_given_max.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int,
+                                                             C.c_uint16, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.moss_oracle_swiglu.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.moss_oracle_swiglu_backward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.moss_oracle_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int64, C.c_int64, C.c_void_p]
         L.moss_oracle_weight_init.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.moss_oracle_weight_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
@@ -114,6 +118,38 @@ def quant_act_2level(x_bf16_bits, axis=0, exp_mode=EXP_NEAREST):
     _check(lib().moss_oracle_quant_act_2level(_p(x), rows, cols, cols, axis, exp_mode, _p(q), _p(e), _p(s)),
            "quant_act_2level")
     return q, e, np.float32(s[0])
+
+
+def quant_act_2level_given_max(x_bf16_bits, max_bf16_bits, axis=0, exp_mode=EXP_NEAREST):
+    """quant_act_2level with the tensor maximum of Eq. 1 handed in (BF16 magnitude bits, at least max|x|)."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    rows, cols = x.shape
+    outer, inner = (rows, cols) if axis == 0 else (cols, rows)
+    q = np.empty((outer, inner), np.uint8)
+    e = np.empty((outer, inner // 32), np.uint8)
+    s = np.zeros(1, np.float32)
+    _check(lib().moss_oracle_quant_act_2level_given_max(_p(x), rows, cols, cols, axis, exp_mode, int(max_bf16_bits) & 0x7FFF,
+                                                        _p(q), _p(e), _p(s)), "quant_act_2level_given_max")
+    return q, e, np.float32(s[0])
+
+
+def swiglu(gate_bits, up_bits):
+    """h = silu(gate) * up in double from BF16 bit arrays of equal shape."""
+    g = np.ascontiguousarray(gate_bits, dtype=np.uint16); u = np.ascontiguousarray(up_bits, dtype=np.uint16)
+    assert g.shape == u.shape
+    h = np.empty(g.shape, np.float64)
+    _check(lib().moss_oracle_swiglu(_p(g), _p(u), g.size, _p(h)), "swiglu")
+    return h
+
+
+def swiglu_backward(gate_bits, up_bits, dh_bits):
+    """(d_gate, d_up) in double for the upstream gradient dh of h = silu(gate) * up."""
+    g = np.ascontiguousarray(gate_bits, dtype=np.uint16); u = np.ascontiguousarray(up_bits, dtype=np.uint16)
+    d = np.ascontiguousarray(dh_bits, dtype=np.uint16)
+    assert g.shape == u.shape == d.shape
+    dg = np.empty(g.shape, np.float64); du = np.empty(g.shape, np.float64)
+    _check(lib().moss_oracle_swiglu_backward(_p(g), _p(u), _p(d), g.size, _p(dg), _p(du)), "swiglu_backward")
+    return dg, du
 
 
 def dequant(q, e, s):

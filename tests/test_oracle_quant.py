@@ -57,12 +57,12 @@ def log2_round_exact(ratio, mode):
     return k if Fraction(2) ** k == ratio else k + 1
 
 
-def brute_quant(xbits, axis, mode):
+def brute_quant(xbits, axis, mode, given_max=None):
     x = mi.bf16_bits_to_f32(xbits).astype(np.float64)
     if axis == 1:
         x = x.T
     outer, inner = x.shape
-    amax = np.abs(x).max()
+    amax = np.abs(x).max() if given_max is None else float(given_max)
     s = np.float32(amax) / np.float32(448.0) if amax > 0 else np.float32(1.0)
     with np.errstate(over="ignore"):
         inv_s = np.float32(1.0) / s
@@ -101,6 +101,29 @@ def test_bruteforce_rational_tiny(oracle, axis, mode):
     assert s == sb
     assert np.array_equal(e, eb)
     assert np.array_equal(q, qb)
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_given_maximum(oracle, axis, mode):
+    """The tensor maximum handed in by the producer: with the true maximum the result is that of the
+    searching quantizer; with a larger bound it is Eq. 1-2 with that bound (exact-rational brute force);
+    a value below max|x| is refused."""
+    rng = np.random.default_rng(90 + axis + 2 * mode)
+    x = rng.standard_normal((32, 64)).astype(np.float32) * np.exp(rng.uniform(-5, 2, (32, 1))).astype(np.float32)
+    xb = mi.f32_to_bf16_bits(x)
+    true_bits = int((xb & 0x7FFF).max())
+    q, e, s = oracle.quant_act_2level(xb, axis, mode)
+    q1, e1, s1 = oracle.quant_act_2level_given_max(xb, true_bits, axis, mode)
+    assert s1 == s and np.array_equal(q1, q) and np.array_equal(e1, e)
+    for bigger in (true_bits + 1, true_bits + 37, true_bits + 3 * 128):      # next value, same binade, three binades up
+        bound = float(mi.bf16_bits_to_f32(np.array([bigger], np.uint16))[0])
+        q2, e2, s2 = oracle.quant_act_2level_given_max(xb, bigger, axis, mode)
+        qb, eb, sb = brute_quant(xb, axis, mode, given_max=bound)
+        assert s2 == sb and s2 > s
+        assert np.array_equal(e2, eb) and np.array_equal(q2, qb)
+    with pytest.raises(Exception):
+        oracle.quant_act_2level_given_max(xb, true_bits - 1, axis, mode)
 
 
 @pytest.mark.parametrize("name", ["zeros", "zero_groups", "one_outlier", "signed_zeros", "tiny", "tiny_zero_groups",
