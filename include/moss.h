@@ -100,6 +100,46 @@ int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_
  * serialised on one stream. */
 void moss_quant_set_poll_limit(unsigned polls);
 
+/* The same quantizer for a tensor whose producer already knows a bound of |X| (Sec. 3.1, Eq. 1:
+ * the global scale is the largest of the group scales, s = max|X| / 448; a kernel that writes X can
+ * keep the running maximum of what it writes, and the search for it, one extra pass over X, falls
+ * away).
+ *   x_absmax_bits  device pointer to one 32-bit word: the BF16 bit pattern, sign bit cleared, of a
+ *                  value >= max|X| (what an unsigned atomic maximum over `bits & 0x7FFF` of every
+ *                  element written leaves; moss_swiglu_bf16 below writes such a word).  With
+ *                  exactly max|X| every output equals that of moss_quant_act_2level; with a larger
+ *                  bound the outputs are Eq. 1-2 evaluated with the bound in place of max|X|; with
+ *                  a smaller value or a non-finite pattern the outputs are unspecified.
+ * Everything else as above; no workspace; one launch, X is read once.                           */
+int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                                    const uint32_t *x_absmax_bits,
+                                    uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
+                                    float *s_global, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * SwiGLU, the BF16 producer in front of the down projection's quantizer (the paper keeps the
+ * non-linear layers in BF16, Sec. 4.1; fusing the search for max|X| into the producer is what
+ * makes the quantizer of Sec. 3.1 a single pass over its input):
+ *      h = silu(gate) * up,   silu(g) = g / (1 + exp(-g)),
+ * evaluated in FP32 and rounded once to BF16 (round to nearest even; the FP32 evaluation is
+ * within a few FP32 ulp of the exact value, so h is the correctly rounded BF16 value except
+ * where the exact value lies within ~2^-20 relative of a rounding boundary, and then one BF16
+ * ulp off).  *h_absmax_bits receives the largest `bits & 0x7FFF` over the h written: exactly
+ * max|h| as a BF16 bit pattern, ready for moss_quant_act_2level_given_max.
+ *
+ * Backward, for an upstream gradient dh (BF16):
+ *      d_up = dh * silu(gate),   d_gate = dh * up * sig(gate) * (1 + gate * (1 - sig(gate))),
+ * sig(g) = 1 / (1 + exp(-g)), both rounded once to BF16, each with its own maximum word.
+ *
+ * gate, up, dh, h, d_gate, d_up: BF16 [rows x cols], all with row stride `ld` elements
+ * (ld >= cols, ld % 8 == 0, cols % 8 == 0, 16-byte aligned); non-finite inputs are not supported.
+ * The maximum words are device memory, written (not accumulated) by the call.                     */
+int moss_swiglu_bf16(const void *gate, const void *up, int64_t rows, int64_t cols, int64_t ld,
+                     void *h, uint32_t *h_absmax_bits, void *stream);
+int moss_swiglu_bf16_backward(const void *gate, const void *up, const void *dh, int64_t rows, int64_t cols, int64_t ld,
+                              void *d_gate, void *d_up, uint32_t *d_gate_absmax_bits, uint32_t *d_up_absmax_bits,
+                              void *stream);
+
 /* ---------------------------------------------------------------------------
  * Per-tensor FP8 weights with automatic scaling  (paper Sec. 3.2, Eq. 6 and the
  * interval re-scaling of its last paragraph; AdamW as in Sec. 2.2 Eq. 3; App. C).

@@ -58,6 +58,9 @@ def load():
     L.moss_quant_workspace_bytes.restype = sz
     L.moss_quant_workspace_bytes.argtypes = [i64, i64, u32]
     L.moss_quant_act_2level.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moss_quant_act_2level_given_max.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp, vp]
+    L.moss_swiglu_bf16.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
+    L.moss_swiglu_bf16_backward.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp]
     L.moss_quant_set_poll_limit.restype = None
     L.moss_quant_set_poll_limit.argtypes = [u32]
     L.moss_weight_workspace_bytes.restype = sz
@@ -126,6 +129,76 @@ def quant_act_2level(x, flags=MOSS_Q_ROW, out=None, workspace=None):
                                  _ptr(s), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "moss_quant_act_2level")
     return dict(q_row=q_row, e_row=e_row, q_col=q_col, e_col=e_col, s=s)
+
+
+def quant_act_2level_given_max(x, absmax_bits, flags=MOSS_Q_ROW, out=None):
+    """quant_act_2level for a tensor whose producer left a bound of max|x| (BF16 magnitude bits) in the
+    one-element int32 device tensor `absmax_bits`: one launch, x read once, no workspace."""
+    import torch
+    L = load()
+    rows, cols = x.shape
+    assert x.dtype == torch.bfloat16 and x.is_cuda and x.stride(1) == 1
+    assert absmax_bits.dtype == torch.int32 and absmax_bits.is_cuda and absmax_bits.numel() == 1
+    dev = x.device
+    out = out or {}
+    u8 = torch.uint8
+    want_row, want_col = bool(flags & MOSS_Q_ROW), bool(flags & MOSS_Q_COL)
+    q_row = out.get("q_row") if want_row else None
+    e_row = out.get("e_row") if want_row else None
+    q_col = out.get("q_col") if want_col else None
+    e_col = out.get("e_col") if want_col else None
+    if want_row and q_row is None:
+        q_row = torch.empty((rows, cols), dtype=u8, device=dev)
+        e_row = torch.empty((rows, cols // 32), dtype=u8, device=dev)
+    if want_col and q_col is None:
+        q_col = torch.empty((cols, rows), dtype=u8, device=dev)
+        e_col = torch.empty((cols, rows // 32), dtype=u8, device=dev)
+    s = out.get("s")
+    if s is None:
+        s = torch.empty(1, dtype=torch.float32, device=dev)
+    rc = L.moss_quant_act_2level_given_max(_ptr(x), rows, cols, x.stride(0), flags, _ptr(absmax_bits), _ptr(q_row), _ptr(e_row),
+                                           _ptr(q_col), _ptr(e_col), _ptr(s), _stream())
+    _check(rc, "moss_quant_act_2level_given_max")
+    return dict(q_row=q_row, e_row=e_row, q_col=q_col, e_col=e_col, s=s)
+
+
+def swiglu_bf16(gate, up, h=None, absmax_bits=None):
+    """h = silu(gate) * up (BF16) and max|h| as BF16 magnitude bits in a one-element int32 tensor."""
+    import torch
+    L = load()
+    rows, cols = gate.shape
+    for t in (gate, up):
+        assert t.dtype == torch.bfloat16 and t.is_cuda and t.stride(1) == 1 and t.shape == gate.shape and t.stride(0) == gate.stride(0)
+    if h is None:
+        h = torch.empty_strided((rows, cols), (gate.stride(0), 1), dtype=torch.bfloat16, device=gate.device)
+    assert h.stride(0) == gate.stride(0) and h.stride(1) == 1
+    if absmax_bits is None:
+        absmax_bits = torch.empty(1, dtype=torch.int32, device=gate.device)
+    rc = L.moss_swiglu_bf16(_ptr(gate), _ptr(up), rows, cols, gate.stride(0), _ptr(h), _ptr(absmax_bits), _stream())
+    _check(rc, "moss_swiglu_bf16")
+    return h, absmax_bits
+
+
+def swiglu_bf16_backward(gate, up, dh, d_gate=None, d_up=None, d_gate_absmax_bits=None, d_up_absmax_bits=None):
+    """(d_gate, d_up, their maximum words) for the upstream gradient dh of h = silu(gate) * up."""
+    import torch
+    L = load()
+    rows, cols = gate.shape
+    ld = gate.stride(0)
+    for t in (gate, up, dh):
+        assert t.dtype == torch.bfloat16 and t.is_cuda and t.stride(1) == 1 and t.shape == gate.shape and t.stride(0) == ld
+    mk = lambda: torch.empty_strided((rows, cols), (ld, 1), dtype=torch.bfloat16, device=gate.device)
+    d_gate = mk() if d_gate is None else d_gate
+    d_up = mk() if d_up is None else d_up
+    assert d_gate.stride(0) == ld and d_up.stride(0) == ld
+    if d_gate_absmax_bits is None:
+        d_gate_absmax_bits = torch.empty(1, dtype=torch.int32, device=gate.device)
+    if d_up_absmax_bits is None:
+        d_up_absmax_bits = torch.empty(1, dtype=torch.int32, device=gate.device)
+    rc = L.moss_swiglu_bf16_backward(_ptr(gate), _ptr(up), _ptr(dh), rows, cols, ld, _ptr(d_gate), _ptr(d_up),
+                                     _ptr(d_gate_absmax_bits), _ptr(d_up_absmax_bits), _stream())
+    _check(rc, "moss_swiglu_bf16_backward")
+    return d_gate, d_up, d_gate_absmax_bits, d_up_absmax_bits
 
 
 def quant_set_poll_limit(polls):

@@ -709,6 +709,43 @@ extern "C" size_t moss_quant_workspace_bytes(int64_t rows, int64_t cols, unsigne
     return (size_t)(moss::kMaxPartials + moss::kSyncWords) * sizeof(uint32_t);
 }
 
+// The launch that converts: k_quant_row for the row grouping alone, k_quant_tile as soon as the transposed
+// grouping is wanted.  `partial` holds n_partial candidate maxima (BF16 magnitude bits) that every workgroup folds.
+static int launch_codes(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, bool want_row, bool want_col,
+                        bool ceil_mode, const uint32_t *partial, int n_partial, uint8_t *q_row, uint8_t *e_row,
+                        uint8_t *q_col, uint8_t *e_col, float *s_global, hipStream_t st)
+{
+    using namespace moss;
+    const int chunks_per_row = (int)(cols / 8);
+    const int64_t n_chunks = rows * chunks_per_row;
+    const int dense = (ld == cols);
+    if (want_row && !want_col) {
+        const int64_t per_block = (int64_t)kQuantThreads * kRowUnroll;
+        const int64_t blocks = (n_chunks + per_block - 1) / per_block;
+        if (blocks > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
+        if (ceil_mode)
+            hipLaunchKernelGGL(k_quant_row<true>, dim3((unsigned)blocks), dim3(kQuantThreads), 0, st, x, n_chunks,
+                               chunks_per_row, ld, dense, partial, n_partial, q_row, e_row, s_global);
+        else
+            hipLaunchKernelGGL(k_quant_row<false>, dim3((unsigned)blocks), dim3(kQuantThreads), 0, st, x, n_chunks,
+                               chunks_per_row, ld, dense, partial, n_partial, q_row, e_row, s_global);
+        MOSS_LAUNCH_CHECK();
+    }
+    if (want_col) {
+        const int64_t gx = (cols + kTile - 1) / kTile, gy = (rows + kTile - 1) / kTile;
+        if (gy > 65535 || gx > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
+        const dim3 grid((unsigned)gx, (unsigned)gy), block(kQuantThreads);
+#define MOSS_LAUNCH_TILE(R, C)                                                                                          \
+    hipLaunchKernelGGL((k_quant_tile<R, C>), grid, block, 0, st, x, rows, cols, ld, partial, n_partial, q_row, e_row, q_col, \
+                       e_col, s_global)
+        if (want_row) { if (ceil_mode) MOSS_LAUNCH_TILE(true, true); else MOSS_LAUNCH_TILE(true, false); }
+        else          { if (ceil_mode) MOSS_LAUNCH_TILE(false, true); else MOSS_LAUNCH_TILE(false, false); }
+#undef MOSS_LAUNCH_TILE
+        MOSS_LAUNCH_CHECK();
+    }
+    return MOSS_OK;
+}
+
 extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
                                      uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
                                      float *s_global, void *workspace, size_t workspace_bytes, void *stream)
@@ -762,29 +799,29 @@ extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t c
                        partial);
     MOSS_LAUNCH_CHECK();
 
-    if (want_row && !want_col) {
-        const int64_t per_block = (int64_t)kQuantThreads * kRowUnroll;
-        const int64_t blocks = (n_chunks + per_block - 1) / per_block;
-        if (blocks > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
-        if (ceil_mode)
-            hipLaunchKernelGGL(k_quant_row<true>, dim3((unsigned)blocks), dim3(kQuantThreads), 0, st, x, n_chunks,
-                               chunks_per_row, ld, dense, partial, n_partial, q_row, e_row, s_global);
-        else
-            hipLaunchKernelGGL(k_quant_row<false>, dim3((unsigned)blocks), dim3(kQuantThreads), 0, st, x, n_chunks,
-                               chunks_per_row, ld, dense, partial, n_partial, q_row, e_row, s_global);
-        MOSS_LAUNCH_CHECK();
-    }
-    if (want_col) {
-        const int64_t gx = (cols + kTile - 1) / kTile, gy = (rows + kTile - 1) / kTile;
-        if (gy > 65535 || gx > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
-        const dim3 grid((unsigned)gx, (unsigned)gy), block(kQuantThreads);
-#define MOSS_LAUNCH_TILE(R, C)                                                                                          \
-    hipLaunchKernelGGL((k_quant_tile<R, C>), grid, block, 0, st, x, rows, cols, ld, partial, n_partial, q_row, e_row, q_col, \
-                       e_col, s_global)
-        if (want_row) { if (ceil_mode) MOSS_LAUNCH_TILE(true, true); else MOSS_LAUNCH_TILE(true, false); }
-        else          { if (ceil_mode) MOSS_LAUNCH_TILE(false, true); else MOSS_LAUNCH_TILE(false, false); }
-#undef MOSS_LAUNCH_TILE
-        MOSS_LAUNCH_CHECK();
-    }
-    return MOSS_OK;
+    return launch_codes(x, rows, cols, ld, want_row, want_col, ceil_mode, partial, n_partial, q_row, e_row, q_col, e_col,
+                        s_global, st);
+}
+
+extern "C" int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                                               const uint32_t *x_absmax_bits, uint8_t *q_row, uint8_t *e_row,
+                                               uint8_t *q_col, uint8_t *e_col, float *s_global, void *stream)
+{
+    using namespace moss;
+    const bool want_row = flags & MOSS_Q_ROW, want_col = flags & MOSS_Q_COL, ceil_mode = flags & MOSS_EXP_CEIL;
+    if (flags & ~(MOSS_Q_ROW | MOSS_Q_COL | MOSS_EXP_CEIL)) return MOSS_ERR_UNSUPPORTED;
+    if (!want_row && !want_col) return MOSS_ERR_UNSUPPORTED;
+    if (!x_bf16 || !s_global || !x_absmax_bits) return MOSS_ERR_NULL;
+    if (want_row && (!q_row || !e_row)) return MOSS_ERR_NULL;
+    if (want_col && (!q_col || !e_col)) return MOSS_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || cols % kGroup || ld < cols) return MOSS_ERR_SHAPE;
+    if (want_col && rows % kGroup) return MOSS_ERR_SHAPE;
+    if (rows * (cols / 8) >= ((int64_t)1 << 40)) return MOSS_ERR_SHAPE;
+    if (ld % 8 || !moss_aligned16(x_bf16)) return MOSS_ERR_ALIGN;
+    if (want_row && !moss_aligned16(q_row)) return MOSS_ERR_ALIGN;
+    if (want_col && !moss_aligned16(q_col)) return MOSS_ERR_ALIGN;
+    if (((uintptr_t)s_global & 3) || ((uintptr_t)x_absmax_bits & 3)) return MOSS_ERR_ALIGN;
+    // the producer's word takes the place of the partial maxima: one candidate, nothing to search
+    return launch_codes((const uint16_t *)x_bf16, rows, cols, ld, want_row, want_col, ceil_mode, x_absmax_bits, 1, q_row,
+                        e_row, q_col, e_col, s_global, (hipStream_t)stream);
 }

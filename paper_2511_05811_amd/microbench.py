@@ -7,6 +7,8 @@
     python -m paper_2511_05811_amd.microbench snr       # Sec. 3.1 Eq. 3 / SNR table: per-tensor vs two-level microscaling
     python -m paper_2511_05811_amd.microbench block     # Sec. 4 setting, one decoder block: tokens/s with the linears on the
                                                          # FP8 path vs BF16 GEMMs (attention, norms, SwiGLU: BF16 torch ops)
+    python -m paper_2511_05811_amd.microbench producer  # SwiGLU that also hands the tensor maximum to the quantizer (Sec. 3.1,
+                                                         # Eq. 1 without the search): one pass over h instead of two
     python -m paper_2511_05811_amd.microbench limits    # what the machine allows: GEMM rate and shader clock by operand
                                                          # content (power limit), plain device-copy bandwidth
 
@@ -249,6 +251,48 @@ def block(moss, torch, small=False):
     return out
 
 
+def producer(moss, torch, small=False):
+    """h = silu(gate) * up followed by the two-level quantization of h (both groupings) at the size of a
+    LLaMA-7B feed-forward activation: torch's two elementwise kernels plus the searching quantizer against
+    the library's SwiGLU, which leaves max|h| behind, plus the quantizer that takes it."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(45)
+    rows, cols = (256, 512) if small else (8192, 11008)
+    bf16 = torch.bfloat16
+    g = (torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) * 2.0).to(bf16)
+    u = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32).to(bf16)
+    d = (torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) * 1e-3).to(bf16)
+    both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL
+    u8 = torch.uint8
+    out = dict(q_row=torch.empty((rows, cols), dtype=u8, device=dev), e_row=torch.empty((rows, cols // 32), dtype=u8, device=dev),
+               q_col=torch.empty((cols, rows), dtype=u8, device=dev), e_col=torch.empty((cols, rows // 32), dtype=u8, device=dev),
+               s=torch.empty(1, dtype=torch.float32, device=dev))
+    ws = torch.empty(max(16, moss.load().moss_quant_workspace_bytes(rows, cols, both)), dtype=u8, device=dev)
+    h = torch.empty_like(g)
+    word = torch.empty(1, dtype=torch.int32, device=dev)
+    dg, du = torch.empty_like(g), torch.empty_like(g)
+    wg, wu = torch.empty(1, dtype=torch.int32, device=dev), torch.empty(1, dtype=torch.int32, device=dev)
+    reps = 3 if small else 10
+    n = rows * cols
+    r = {}
+    r["torch_silu_mul_ms"], _ = _time_ms(torch, lambda: torch.mul(torch.nn.functional.silu(g), u, out=h), reps)
+    r["quant_searching_ms"], _ = _time_ms(torch, lambda: moss.quant_act_2level(h, both, out=out, workspace=ws), reps)
+    r["swiglu_with_max_ms"], _ = _time_ms(torch, lambda: moss.swiglu_bf16(g, u, h=h, absmax_bits=word), reps)
+    r["quant_given_max_ms"], _ = _time_ms(torch, lambda: moss.quant_act_2level_given_max(h, word, both, out=out), reps)
+    r["swiglu_backward_with_max_ms"], _ = _time_ms(
+        torch, lambda: moss.swiglu_bf16_backward(g, u, d, d_gate=dg, d_up=du, d_gate_absmax_bits=wg, d_up_absmax_bits=wu), reps)
+    r = {k: round(v, 4) for k, v in r.items()}
+    r["swiglu_gbs"] = round(n * 6.0 / (r["swiglu_with_max_ms"] * 1e-3) / 1e9, 1)                 # 2 x 2 B in, 2 B out
+    r["swiglu_backward_gbs"] = round(n * 10.0 / (r["swiglu_backward_with_max_ms"] * 1e-3) / 1e9, 1)   # 3 x 2 B in, 2 x 2 B out
+    r["quant_given_max_gbs"] = round(n * 4.0625 / (r["quant_given_max_ms"] * 1e-3) / 1e9, 1)
+    r["chain_torch_then_search_ms"] = round(r["torch_silu_mul_ms"] + r["quant_searching_ms"], 4)
+    r["chain_fused_ms"] = round(r["swiglu_with_max_ms"] + r["quant_given_max_ms"], 4)
+    return {"table": "producer", "shape": [rows, cols], "unit": "ms", "times": r,
+            "note": "torch_silu_mul: torch.nn.functional.silu then torch.mul (two elementwise kernels); the searching quantizer "
+                    "reads h twice at this size (172 MiB), the one given the maximum once"}
+
+
 class _ClockPoller:
     """Samples the shader clock with `rocm-smi --showclocks` (a child process that only reads sysfs)
     while the GPU works."""
@@ -329,7 +373,7 @@ def limits(moss, torch, small=False):
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["scaling", "gemm", "snr", "limits", "block"])
+    ap.add_argument("table", choices=["scaling", "gemm", "snr", "limits", "block", "producer"])
     ap.add_argument("--small", action="store_true", help="tiny shapes (used by the tests)")
     a = ap.parse_args(argv)
     import torch
@@ -337,7 +381,7 @@ def main(argv=None):
     if not torch.cuda.is_available():
         print("microbench needs the MI355X", file=sys.stderr)
         return 2
-    res = {"scaling": scaling, "gemm": gemm, "snr": snr, "limits": limits, "block": block}[a.table](moss, torch, a.small)
+    res = {"scaling": scaling, "gemm": gemm, "snr": snr, "limits": limits, "block": block, "producer": producer}[a.table](moss, torch, a.small)
     print(json.dumps(res))
     return 0
 

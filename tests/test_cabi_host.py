@@ -59,6 +59,31 @@ def test_quant_argument_validation(L):
     assert q(FAKE, 32, 32, 32, 64) == 5                   # unknown flag
 
 
+def test_producer_argument_validation(L):
+    q = lambda x, rows, cols, ld, flags, mx=FAKE, qr=FAKE, er=FAKE, qc=FAKE, ec=FAKE, s=FAKE: \
+        L.moss_quant_act_2level_given_max(x, rows, cols, ld, flags, mx, qr, er, qc, ec, s, None)
+    assert q(None, 32, 32, 32, 1) == 1
+    assert q(FAKE, 32, 32, 32, 1, mx=None) == 1           # no maximum word
+    assert q(FAKE, 32, 32, 32, 3, ec=None) == 1
+    assert q(FAKE, 32, 48, 48, 1) == 2
+    assert q(FAKE, 48, 32, 32, 2) == 2
+    assert q(FAKE, 32, 32, 36, 1) == 3
+    assert q(FAKE, 32, 32, 32, 1, mx=FAKE + 2) == 3       # misaligned maximum word
+    assert q(FAKE, 32, 32, 32, 0) == 5
+    f = lambda g=FAKE, u=FAKE, rows=4, cols=8, ld=8, h=FAKE, m=FAKE: L.moss_swiglu_bf16(g, u, rows, cols, ld, h, m, None)
+    assert f(g=None) == 1 and f(m=None) == 1
+    assert f(cols=12, ld=16) == 2                         # cols not a multiple of 8
+    assert f(rows=0) == 2 and f(ld=4) == 2
+    assert f(ld=12, cols=8) == 3                          # ld not a multiple of 8
+    assert f(h=FAKE + 8) == 3
+    b = lambda dh=FAKE, dg=FAKE, du=FAKE, mg=FAKE, mu=FAKE + 4, cols=8: \
+        L.moss_swiglu_bf16_backward(FAKE, FAKE, dh, 4, cols, 8, dg, du, mg, mu, None)
+    assert b(dh=None) == 1 and b(mu=None) == 1
+    assert b(cols=4) == 2
+    assert b(du=FAKE + 2) == 3
+    assert b(mg=FAKE, mu=FAKE) == 5                       # one word for two maxima
+
+
 def test_weight_argument_validation(L):
     args = moss.AdamWArgs(3e-4, 0.9, 0.95, 1e-8, 0.1, 0.1, 0.05, 0.1, 0.05, 1.0, 500, 1)
     big = 1 << 20

@@ -36,6 +36,11 @@ def test_snr_table_small():
     assert res["moss_nearest"] > 10.0
 
 
+def test_producer_table_small():
+    t = microbench.producer(moss, torch, small=True)["times"]
+    assert t["swiglu_with_max_ms"] > 0 and t["quant_given_max_ms"] > 0 and t["chain_fused_ms"] > 0
+
+
 def test_limits_table_small():
     res = microbench.limits(moss, torch, small=True)
     assert len(res["gemm_by_operand_content"]) == 3 and all(r["tflops"] > 0 for r in res["gemm_by_operand_content"])
