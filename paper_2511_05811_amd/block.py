@@ -12,7 +12,30 @@ linear layers differ:
               FP32 master weights followed by a BF16 copy.
 
 Q, K and V are one fused hidden -> 3 hidden linear; gate and up are separate linears.
+
+SwiGLU is the library's BF16 kernel in both arms (`swiglu="fused"`, the default) or torch's
+silu and mul (`swiglu="torch"`).  In the "moss" arm the fused kernel also hands the maximum of
+what it wrote (h forward, d_gate and d_up backward) to the quantizer of the linear that consumes
+it, which then reads that tensor once instead of twice.
 """
+
+
+class _MaxWords:
+    """Side channel from a producer to the quantizer of the tensor it wrote: the device word that
+    holds the tensor's maximum, keyed by the tensor's storage."""
+
+    def __init__(self):
+        self.words = {}
+
+    def put(self, tensor, word):
+        self.words[tensor.data_ptr()] = (tuple(tensor.shape), word)
+
+    def take(self, tensor):
+        e = self.words.pop(tensor.data_ptr(), None)
+        return e[1] if e is not None and e[0] == tuple(tensor.shape) else None
+
+    def clear(self):
+        self.words.clear()
 def _adamw_args(moss, t, lr=3e-4, interval=500):
     import numpy as np
     b1, b2 = float(np.float32(0.9)), float(np.float32(0.95))
@@ -22,9 +45,9 @@ def _adamw_args(moss, t, lr=3e-4, interval=500):
 class _MossLinear:
     """FP32 master weight [N x K] with its FP8 copies, optimizer state and per-layer buffers."""
 
-    def __init__(self, moss, torch, tokens, k, n, gen, dev):
+    def __init__(self, moss, torch, tokens, k, n, gen, dev, words=None):
         u8, f32 = torch.uint8, torch.float32
-        self.moss, self.k, self.n = moss, k, n
+        self.moss, self.k, self.n, self.words = moss, k, n, words
         self.w = torch.randn((n, k), generator=gen, device=dev, dtype=f32) * 0.02
         self.m = torch.zeros_like(self.w)
         self.v = torch.zeros_like(self.w)
@@ -56,7 +79,11 @@ def _moss_linear_fn(torch):
             moss = layer.moss
             both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL
             x = x.contiguous()
-            moss.quant_act_2level(x, both, out=layer.qx, workspace=layer.ws_q)
+            word = layer.words.take(x) if layer.words is not None else None
+            if word is not None:
+                moss.quant_act_2level_given_max(x, word, both, out=layer.qx)
+            else:
+                moss.quant_act_2level(x, both, out=layer.qx, workspace=layer.ws_q)
             ctx.layer = layer
             return moss.gemm_fp8_mx(layer.qx["q_row"], layer.qx["e_row"], layer.qx["s"], layer.wq, None, layer.s_w)
 
@@ -66,11 +93,38 @@ def _moss_linear_fn(torch):
             moss = layer.moss
             both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL
             dy = dy.contiguous()
-            moss.quant_act_2level(dy, both, out=layer.qdy, workspace=layer.ws_q)
+            word = layer.words.take(dy) if layer.words is not None else None
+            if word is not None:
+                moss.quant_act_2level_given_max(dy, word, both, out=layer.qdy)
+            else:
+                moss.quant_act_2level(dy, both, out=layer.qdy, workspace=layer.ws_q)
             dx = moss.gemm_fp8_mx(layer.qdy["q_row"], layer.qdy["e_row"], layer.qdy["s"], layer.wq_t, None, layer.s_w)
             moss.gemm_fp8_mx(layer.qdy["q_col"], layer.qdy["e_col"], layer.qdy["s"], layer.qx["q_col"], layer.qx["e_col"],
                              layer.qx["s"], out=layer.dw, out_dtype=torch.float32)
             return dx, None
+    return Fn
+
+
+def _swiglu_fn(moss, torch):
+    class Fn(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, gate, up, words):
+            gate, up = gate.contiguous(), up.contiguous()
+            h, word = moss.swiglu_bf16(gate, up)
+            ctx.save_for_backward(gate, up)
+            ctx.words = words
+            if words is not None:
+                words.put(h, word)
+            return h
+
+        @staticmethod
+        def backward(ctx, dh):
+            gate, up = ctx.saved_tensors
+            dg, du, wg, wu = moss.swiglu_bf16_backward(gate, up, dh.contiguous())
+            if ctx.words is not None:
+                ctx.words.put(dg, wg)
+                ctx.words.put(du, wu)
+            return dg, du, None
     return Fn
 
 
@@ -102,9 +156,11 @@ def _bf16_linear_fn(torch):
 class DecoderBlock:
     """hidden -> attention -> SwiGLU FFN, pre-norm, as in LLaMA."""
 
-    def __init__(self, moss, torch, arm, batch, seq, hidden, heads, ffn, seed=5):
-        assert arm in ("moss", "bf16") and hidden % heads == 0
+    def __init__(self, moss, torch, arm, batch, seq, hidden, heads, ffn, seed=5, swiglu="fused"):
+        assert arm in ("moss", "bf16") and hidden % heads == 0 and swiglu in ("fused", "torch")
         self.torch, self.moss, self.arm = torch, moss, arm
+        self.words = _MaxWords() if (arm == "moss" and swiglu == "fused") else None
+        self.swiglu = _swiglu_fn(moss, torch) if swiglu == "fused" else None
         self.batch, self.seq, self.hidden, self.heads, self.ffn = batch, seq, hidden, heads, ffn
         dev = torch.device("cuda:0")
         gen = torch.Generator(device=dev)
@@ -112,7 +168,7 @@ class DecoderBlock:
         tokens = batch * seq
         shapes = [("qkv", hidden, 3 * hidden), ("o", hidden, hidden), ("gate", hidden, ffn), ("up", hidden, ffn), ("down", ffn, hidden)]
         if arm == "moss":
-            self.lin = {n: _MossLinear(moss, torch, tokens, k, nn, gen, dev) for n, k, nn in shapes}
+            self.lin = {n: _MossLinear(moss, torch, tokens, k, nn, gen, dev, self.words) for n, k, nn in shapes}
             self.fn = _moss_linear_fn(torch)
         else:
             self.lin = {n: _Bf16Linear(torch, k, nn, gen, dev) for n, k, nn in shapes}
@@ -147,12 +203,17 @@ class DecoderBlock:
         att = F.scaled_dot_product_attention(self._rope(q), self._rope(k), v, is_causal=True)
         h = x + fn.apply(att.transpose(1, 2).reshape(T, H), lin["o"]).view(B, S, H)
         b = F.rms_norm(h, (H,), self.g2, 1e-5).view(T, H)
-        f = F.silu(fn.apply(b, lin["gate"])) * fn.apply(b, lin["up"])
+        if self.swiglu is not None:
+            f = self.swiglu.apply(fn.apply(b, lin["gate"]), fn.apply(b, lin["up"]), self.words)
+        else:
+            f = F.silu(fn.apply(b, lin["gate"])) * fn.apply(b, lin["up"])
         return h + fn.apply(f, lin["down"]).view(B, S, H)
 
     def train_step(self):
         """forward, backward with the fixed upstream gradient, optimizer step on the five weights"""
         self.t += 1
+        if self.words is not None:
+            self.words.clear()
         x = self.x.detach().requires_grad_(True)
         out = self.forward(x)
         out.backward(self.upstream)
