@@ -122,9 +122,9 @@ int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows, int64_t co
  * makes the quantizer of Sec. 3.1 a single pass over its input):
  *      h = silu(gate) * up,   silu(g) = g / (1 + exp(-g)),
  * evaluated in FP32 and rounded once to BF16 (round to nearest even; the FP32 evaluation is
- * within a few FP32 ulp of the exact value, so h is the correctly rounded BF16 value except
- * where the exact value lies within ~2^-20 relative of a rounding boundary, and then one BF16
- * ulp off).  *h_absmax_bits receives the largest `bits & 0x7FFF` over the h written: exactly
+ * within ~2^-18 relative of the exact value, so h is the correctly rounded BF16 value except
+ * where the exact value lies that close to a rounding boundary, and then it is the BF16
+ * neighbour: |h - exact| <= (1/2 + 2^-9) BF16 ulp).  *h_absmax_bits receives the largest `bits & 0x7FFF` over the h written: exactly
  * max|h| as a BF16 bit pattern, ready for moss_quant_act_2level_given_max.
  *
  * Backward, for an upstream gradient dh (BF16):
