@@ -86,3 +86,57 @@ def test_quantize_gemm_update_chain_in_a_graph():
         assert np.isfinite(scratch)
         for a, b, name in zip(got, want[t - 1], ("y", "dx", "dw", "w", "m", "v", "wq", "wq_t", "state")):
             assert torch.equal(a, b), (t, name)
+
+
+def test_producer_chain_in_a_graph():
+    """SwiGLU (which clears and fills its maximum word with kernels, no memset) followed by the quantizer that
+    takes the word: captured once, replayed on changing inputs, each replay equal to the eager result."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(78)
+    rows, cols = 1024, 1536
+    bf16 = torch.bfloat16
+    both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL
+    g = torch.empty((rows, cols), dtype=bf16, device=dev)
+    u = torch.empty((rows, cols), dtype=bf16, device=dev)
+    d = torch.empty((rows, cols), dtype=bf16, device=dev)
+
+    def fill(seed_scale):
+        g.copy_((torch.randn((rows, cols), generator=gen, device=dev) * seed_scale).to(bf16))
+        u.copy_(torch.randn((rows, cols), generator=gen, device=dev).to(bf16))
+        d.copy_((torch.randn((rows, cols), generator=gen, device=dev) * 1e-2).to(bf16))
+
+    class Bufs:
+        def __init__(self):
+            self.h = torch.empty((rows, cols), dtype=bf16, device=dev)
+            self.dg, self.du = torch.empty_like(self.h), torch.empty_like(self.h)
+            self.w = [torch.empty(1, dtype=torch.int32, device=dev) for _ in range(3)]
+            self.q = None
+
+        def run(self):
+            moss.swiglu_bf16(g, u, h=self.h, absmax_bits=self.w[0])
+            self.q = moss.quant_act_2level_given_max(self.h, self.w[0], both, out=self.q)
+            moss.swiglu_bf16_backward(g, u, d, d_gate=self.dg, d_up=self.du, d_gate_absmax_bits=self.w[1], d_up_absmax_bits=self.w[2])
+
+        def snapshot(self):
+            torch.cuda.synchronize()
+            return [t.clone() for t in (self.h, self.dg, self.du, *self.w, self.q["q_row"], self.q["e_row"], self.q["q_col"],
+                                        self.q["e_col"], self.q["s"])]
+
+    fill(1.0)
+    graphed = Bufs()
+    graphed.run()                        # allocates the quantizer's outputs once, outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+        graphed.run()
+    eager = Bufs()
+    for scale in (0.5, 3.0, 8.0):
+        fill(scale)
+        eager.run()
+        want = eager.snapshot()
+        graph.replay()
+        got = graphed.snapshot()
+        assert np.isfinite(torch.randn(1 << 18, device=dev).sum().item())
+        for i, (a, b) in enumerate(zip(got, want)):
+            assert torch.equal(a, b), (scale, i)

@@ -109,6 +109,21 @@ def test_quantizer_with_the_maximum_handed_in(oracle, shape, flag):
         assert torch.equal(ref[k], got[k]), k
 
 
+def test_quantizer_with_the_maximum_handed_in_on_a_strided_view(oracle):
+    rows, cols, ld = 1056, 2080, 2304
+    full = mi.heavy_tailed_activation(rows, ld, seed=17)
+    xb = np.ascontiguousarray(full[:, :cols])
+    x = bf16_to_gpu(full)[:, :cols]
+    given = int((xb & 0x7FFF).max())
+    got = moss.quant_act_2level_given_max(x, torch.tensor([given], dtype=torch.int32, device=x.device), ROW | COL)
+    torch.cuda.synchronize()
+    qr, er, s = oracle.quant_act_2level(xb, 0, 0)
+    qc, ec, _ = oracle.quant_act_2level(xb, 1, 0)
+    assert scalar(got["s"]) == s
+    assert np.array_equal(u8(got["q_row"]), qr) and np.array_equal(u8(got["e_row"]), er)
+    assert np.array_equal(u8(got["q_col"]), qc) and np.array_equal(u8(got["e_col"]), ec)
+
+
 def test_swiglu_feeds_the_quantizer_in_one_pass(oracle):
     """The chain the two entry points are for: SwiGLU writes h and its maximum, the quantizer reads h once.
     The codes are those the oracle's quantizer gives for the h the GPU wrote."""
