@@ -3,8 +3,8 @@
  *
  * A plain, slow, obviously-correct implementation of what the MOSS hot path
  * computes (arXiv 2511.05811): two-level microscaled FP8 quantization of
- * activations (Sec. 3.1, Eq. 1-2), per-tensor FP8 weights with the automatic
- * scaling rule fused into an AdamW step (Sec. 2.2 Eq. 3, Sec. 3.2 Eq. 6,
+ * activations (Sec. 3.1, Eq. 2-3), per-tensor FP8 weights with the automatic
+ * scaling rule fused into an AdamW step (Sec. 2.2 Eq. 1, Sec. 3.2 Eq. 10,
  * App. C), and the block-scaled FP8 GEMM with epilogue dequantization
  * (Sec. 3.1, Fig. 3b).
  *
@@ -33,7 +33,7 @@
 #define MOSS_O_BAD_ARG 1
 #define MOSS_O_NONFINITE 2
 
-#define E4M3_MAX 448.0 /* Delta_max of E4M3, Sec. 3.1 below Eq. 1 */
+#define E4M3_MAX 448.0 /* Delta_max of E4M3, Sec. 3.1 below Eq. 2 */
 #define K2 32          /* level-2 group size, Sec. 3.1 ("k2 = 32") */
 
 /* ------------------------------------------------------------------ */
@@ -95,7 +95,7 @@ static double round_to_24_bits(double p)
     return ldexp(r, ex - 24);
 }
 
-/* Level-2 exponent e_i = round(log2(amax_i / amax)) (Eq. 2), evaluated
+/* Level-2 exponent e_i = round(log2(amax_i / amax)) (Eq. 3), evaluated
  * exactly.  mode 0 (nearest, the paper's "closest power of two" in the log
  * domain): the unique integer k with 2^(2k-1) <= (amax_i/amax)^2 < 2^(2k+1).
  * mode 1 (ceil): the smallest k with amax_i <= 2^k * amax.  Squares of BF16
@@ -117,7 +117,7 @@ static int local_exponent(double amax_i, double amax, int mode)
 }
 
 /* ------------------------------------------------------------------ */
-/* Two-level microscaling quantizer (Sec. 3.1, Eq. 1-2 and the quantize /
+/* Two-level microscaling quantizer (Sec. 3.1, Eq. 2-3 and the quantize /
  * dequantize maps Q = round(X / (s*ss_i)), DQ = Q*s*ss_i).
  *
  * x        BF16 bits, rows x cols, row stride ld (elements)
@@ -125,7 +125,7 @@ static int local_exponent(double amax_i, double amax, int mode)
  *             q[rows][cols], e[rows][cols/32]);
  *          1: groups of 32 along the rows, outputs stored transposed
  *             (q[cols][rows], e[cols][rows/32]).
- * exp_mode 0 nearest (Eq. 2), 1 ceil.
+ * exp_mode 0 nearest (Eq. 3), 1 ceil.
  * The global scale s is per tensor and does not depend on axis.        */
 static int quant_with_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, int axis, int exp_mode,
                           double given_max, uint8_t *q, uint8_t *e, float *s_global);
@@ -137,7 +137,7 @@ int moss_oracle_quant_act_2level(const uint16_t *x, int64_t rows, int64_t cols, 
     return quant_with_max(x, rows, cols, ld, axis, exp_mode, -1.0, q, e, s_global);
 }
 
-/* The same with the tensor maximum of Eq. 1 handed in by whoever produced X (BF16 magnitude bits)
+/* The same with the tensor maximum of Eq. 2 handed in by whoever produced X (BF16 magnitude bits)
  * instead of being searched for: it has to be at least max|X|; with exactly max|X| the result is that
  * of moss_oracle_quant_act_2level.                                                                  */
 int moss_oracle_quant_act_2level_given_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld,
@@ -157,7 +157,7 @@ static int quant_with_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t
     if (axis == 0 && cols % K2) return MOSS_O_BAD_ARG;
     if (axis == 1 && rows % K2) return MOSS_O_BAD_ARG;
 
-    /* level 1 (Eq. 1): s_i = amax_i / 448, and s = max_i s_i = amax / 448 */
+    /* level 1 (Eq. 2): s_i = amax_i / 448, and s = max_i s_i = amax / 448 */
     double amax = 0.0;
     for (int64_t r = 0; r < rows; r++)
         for (int64_t c = 0; c < cols; c++) {
@@ -172,7 +172,7 @@ static int quant_with_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t
     float s = 1.0f;                       /* all-zero tensor: s = 1 */
     if (amax > 0.0) s = (float)amax / 448.0f;   /* one IEEE single division */
     float inv_s = 1.0f / s;               /* one IEEE single division */
-    /* Eq. 1 divides by a positive scale, so a zero input has code zero.  For a tensor whose
+    /* Eq. 2 divides by a positive scale, so a zero input has code zero.  For a tensor whose
      * maximum is below 448 * 2^-128 the single-precision reciprocal overflows and 0 * inf
      * would be NaN: the largest finite single stands in for it (nonzero inputs still
      * saturate or round as their true quotient would within a factor the format cannot
@@ -194,7 +194,7 @@ static int quant_with_max(const uint16_t *x, int64_t rows, int64_t cols, int64_t
                 xv[j] = bf16_to_double(x[r * ld + c]);
                 if (fabs(xv[j]) > amax_i) amax_i = fabs(xv[j]);
             }
-            /* level 2 (Eq. 2): ss_i = 2^{e_i}, stored as the E8M0 byte e_i + 127 */
+            /* level 2 (Eq. 3): ss_i = 2^{e_i}, stored as the E8M0 byte e_i + 127 */
             int e_i = local_exponent(amax_i, amax, exp_mode);
             e[o * n_groups + g] = (uint8_t)(e_i + 127);
             for (int j = 0; j < K2; j++) {
@@ -229,40 +229,49 @@ int moss_oracle_dequant(const uint8_t *q, const uint8_t *e, float s,
 /* Weight path: per-tensor FP8 weights with automatic scaling (Sec. 3.2).   */
 
 typedef struct {
-    float s_base;            /* s_0 of Eq. 6: amax(W)/448 at the last max-reduction */
-    float s_cur;             /* scale used by the latest cast, s_t of Eq. 6 */
+    float s_base;            /* s_0 of Eq. 10: amax(W)/448 at the last max-reduction */
+    float s_cur;             /* scale used by the latest cast, s_t of Eq. 10 */
     double cum_lr;           /* sum of (margin * eta) since the last max-reduction ("eta * t") */
     int64_t step;            /* optimizer steps taken */
     int64_t last_rebase;     /* step of the last max-reduction */
     float amax_seen;         /* amax of the weights at the latest cast */
-    uint32_t overflow_count; /* elements the saturating casts clipped (|w/s| > 464, i.e. beyond
-                                what rounds to 448 by itself), cumulative */
+    uint32_t overflow_count; /* elements outside the range the scale covers, |w| > 448 * s_cur
+                                (compared exactly), summed over all casts */
+    uint32_t clipped_count;  /* elements whose code the saturation changed: |fl(w * fl(1/s))| > 464,
+                                the midpoint above 448; summed over all casts */
+    uint32_t reserved;       /* always 0 here (the device library keeps a flag word in this place) */
 } moss_oracle_wstate;
 
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;
     float one_minus_beta1, one_minus_beta2; /* caller-rounded (1-beta) */
     float bias_corr1, bias_corr2;           /* caller-rounded 1-beta^t */
-    float margin;                           /* multiplies eta in Eq. 6; the paper uses 1 */
+    float margin;                           /* multiplies eta in Eq. 10; the paper uses 1 */
     int32_t interval;                       /* max-reduction every `interval` steps; <=0: never */
 } moss_oracle_adamw_args;
 
 /* Q_W = round_E4M3(W / s) with W/s evaluated as one single-precision multiply
  * by fl(1/s); s == 0 (all-zero tensor) maps everything to zero codes.     */
 static void cast_weights(const float *w, int64_t n, float s, uint8_t *wq,
-                         float *amax_out, uint32_t *overflow_add)
+                         float *amax_out, uint32_t *overflow_add, uint32_t *clipped_add)
 {
     float inv_s = s > 0.0f ? 1.0f / s : 0.0f;
     float amax = 0.0f;
-    uint32_t over = 0;
+    uint32_t over = 0, clipped = 0;
+    /* The scale is meant to keep W / s inside [-448, 448] (Sec. 3.2, text under Eq. 10).  An
+     * element breaks that when |w| > 448 * s; the product of a single and 448 is exact in
+     * double, so the comparison is exact.                                                  */
+    const double range = E4M3_MAX * (double)s;
     for (int64_t i = 0; i < n; i++) {
         float y = w[i] * inv_s;
         if (fabsf(w[i]) > amax) amax = fabsf(w[i]);
-        if (fabsf(y) > 464.0f) over++;   /* beyond the values that round to 448 on their own */
+        if ((double)fabsf(w[i]) > range) over++;
+        if (fabsf(y) > 464.0f) clipped++; /* beyond the values that round to 448 on their own */
         if (wq) wq[i] = moss_oracle_e4m3_encode((double)y);
     }
     *amax_out = amax;
     *overflow_add = over;
+    *clipped_add = clipped;
 }
 
 static void transpose_u8(const uint8_t *src, int64_t rows, int64_t cols, uint8_t *dst)
@@ -272,7 +281,7 @@ static void transpose_u8(const uint8_t *src, int64_t rows, int64_t cols, uint8_t
 }
 
 /* Initialisation: s_0 = amax(W_0)/448 by one max-reduction (Sec. 3.2, text
- * under Eq. 6), then the first cast.  w is FP32 [rows x cols].            */
+ * under Eq. 10), then the first cast.  w is FP32 [rows x cols].            */
 int moss_oracle_weight_init(const float *w, int64_t rows, int64_t cols,
                             moss_oracle_wstate *st, uint8_t *wq, uint8_t *wq_t)
 {
@@ -286,19 +295,21 @@ int moss_oracle_weight_init(const float *w, int64_t rows, int64_t cols,
     memset(st, 0, sizeof *st);
     st->s_base = amax / 448.0f;
     st->s_cur = st->s_base;
-    uint32_t over;
-    cast_weights(w, n, st->s_cur, wq, &st->amax_seen, &over);
+    uint32_t over, clipped;
+    cast_weights(w, n, st->s_cur, wq, &st->amax_seen, &over, &clipped);
     st->overflow_count = over;
+    st->clipped_count = clipped;
     if (wq_t) transpose_u8(wq, rows, cols, wq_t);
     return MOSS_O_OK;
 }
 
 /* One optimizer step with the cast fused in.
- *  1. AdamW (Eq. 3), FP32, this operation order, nothing contracted.
- *  2. predict (Eq. 6): cum_lr += margin*eta; s_t = s_0 + cum_lr/448.
+ *  1. AdamW (Eq. 1), FP32, this operation order, nothing contracted.
+ *  2. predict (Eq. 10): cum_lr += margin*eta; s_t = s_0 + cum_lr/448.
  *  3. every `interval` steps re-scale from the true maximum (Sec. 3.2,
  *     last paragraph): s_0 = s_t = amax(W_new)/448, cum_lr = 0.
- *  4. cast W_new with s_t; record amax and the number of saturated elements.
+ *  4. cast W_new with s_t; record amax, the number of elements outside 448 * s_t and the
+ *     number of elements the saturation changed.
  * g is FP32 (g_is_bf16 == 0) or BF16 bits (g_is_bf16 == 1).              */
 int moss_oracle_weight_step(float *w, float *m, float *v, const void *g, int g_is_bf16,
                             int64_t rows, int64_t cols, const moss_oracle_adamw_args *a,
@@ -342,9 +353,10 @@ int moss_oracle_weight_step(float *w, float *m, float *v, const void *g, int g_i
         st->cum_lr = 0.0;
         st->last_rebase = st->step;
     }
-    uint32_t over;
-    cast_weights(w, n, st->s_cur, wq, &st->amax_seen, &over);
+    uint32_t over, clipped;
+    cast_weights(w, n, st->s_cur, wq, &st->amax_seen, &over, &clipped);
     st->overflow_count += over;
+    st->clipped_count += clipped;
     if (wq_t) transpose_u8(wq, rows, cols, wq_t);
     return MOSS_O_OK;
 }
@@ -426,8 +438,6 @@ int moss_oracle_row_norms(int64_t R, int64_t K, const uint8_t *q, const uint8_t 
     return MOSS_O_OK;
 }
 
-/* Quantization SNR in dB (Sec. 3.1, Eq. 3 of that section):
- * 10 log10( sum x^2 / sum (dq - x)^2 ).                                  */
 /* ------------------------------------------------------------------ */
 /* The producer on the input side of the down projection (the paper leaves the non-linear
  * layers in BF16, Sec. 4.1): SwiGLU of a LLaMA feed-forward block,
@@ -461,6 +471,9 @@ int moss_oracle_swiglu_backward(const uint16_t *gate, const uint16_t *up, const 
     return MOSS_O_OK;
 }
 
+/* Quantization SNR in dB (Sec. 3.1, Eq. 4): signal power over noise power,
+ * 10 log10( sum x^2 / sum (dq - x)^2 ) (the expectations of Eq. 4 over the same n elements;
+ * the 1/n cancel).                                                       */
 double moss_oracle_snr_db(const double *x, const double *dq, int64_t n)
 {
     double ps = 0.0, pn = 0.0;

@@ -32,7 +32,8 @@ def build(force=False):
 class WState(C.Structure):
     _fields_ = [("s_base", C.c_float), ("s_cur", C.c_float), ("cum_lr", C.c_double),
                 ("step", C.c_int64), ("last_rebase", C.c_int64),
-                ("amax_seen", C.c_float), ("overflow_count", C.c_uint32)]
+                ("amax_seen", C.c_float), ("overflow_count", C.c_uint32),
+                ("clipped_count", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class AdamWArgs(C.Structure):
@@ -121,7 +122,7 @@ def quant_act_2level(x_bf16_bits, axis=0, exp_mode=EXP_NEAREST):
 
 
 def quant_act_2level_given_max(x_bf16_bits, max_bf16_bits, axis=0, exp_mode=EXP_NEAREST):
-    """quant_act_2level with the tensor maximum of Eq. 1 handed in (BF16 magnitude bits, at least max|x|)."""
+    """quant_act_2level with the tensor maximum of Eq. 2 handed in (BF16 magnitude bits, at least max|x|)."""
     x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
     rows, cols = x.shape
     outer, inner = (rows, cols) if axis == 0 else (cols, rows)

@@ -1,4 +1,4 @@
-"""Pins for the oracle's two-level microscaling quantizer (Sec. 3.1, Eq. 1-2):
+"""Pins for the oracle's two-level microscaling quantizer (Sec. 3.1, Eq. 2-3):
 an exact-rational brute force written independently in Python, the error bound
 the rounding implies, metamorphic relations and a special case that reduces to
 a plain per-tensor library cast."""
@@ -107,7 +107,7 @@ def test_bruteforce_rational_tiny(oracle, axis, mode):
 @pytest.mark.parametrize("mode", [0, 1])
 def test_given_maximum(oracle, axis, mode):
     """The tensor maximum handed in by the producer: with the true maximum the result is that of the
-    searching quantizer; with a larger bound it is Eq. 1-2 with that bound (exact-rational brute force);
+    searching quantizer; with a larger bound it is Eq. 2-3 with that bound (exact-rational brute force);
     a value below max|x| is refused."""
     rng = np.random.default_rng(90 + axis + 2 * mode)
     x = rng.standard_normal((32, 64)).astype(np.float32) * np.exp(rng.uniform(-5, 2, (32, 1))).astype(np.float32)
@@ -275,3 +275,27 @@ def test_moss_snr_vs_per_tensor_cast(oracle):
     snr_moss = oracle.snr_db(x[:, small], dq[:, small])
     snr_tensor = oracle.snr_db(x[:, small], qt[:, small])
     assert snr_moss > snr_tensor + 3.0
+
+
+def test_snr_db_closed_forms(oracle):
+    """Sec. 3.1, Eq. 4: SNR = 10 log10(E|x|^2 / E|dq - x|^2), pinned to values the mathematics fixes."""
+    import math
+    # signal 3^2 + 4^2 = 25, noise 1^2: 10 log10 25 (20 log10 would give 27.96, the swapped ratio -13.98)
+    assert abs(oracle.snr_db(np.array([3.0, 4.0, 0.0]), np.array([3.0, 4.0, 1.0])) - 13.979400086720377) < 1e-12
+    # not symmetric in its arguments: signal 4, noise 1 is 10 log10 4; with the arguments swapped 0 dB
+    assert abs(oracle.snr_db(np.array([2.0, 0.0]), np.array([1.0, 0.0])) - 6.020599913279624) < 1e-12
+    assert abs(oracle.snr_db(np.array([1.0, 0.0]), np.array([2.0, 0.0]))) < 1e-12
+    # a uniform relative error delta on any signal gives -20 log10 delta, whatever the signal
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(4096) * 7.0
+    for k in (1, 4, 10, 20):
+        delta = 2.0 ** -k
+        assert abs(oracle.snr_db(x, x * (1.0 + delta)) - 20.0 * k * math.log10(2.0)) < 1e-9
+        assert abs(oracle.snr_db(np.ones(33), np.ones(33) * (1.0 - delta)) - 20.0 * k * math.log10(2.0)) < 1e-9
+    # the definition with expectations written out (numpy), on unrelated signal and noise
+    dq = x + rng.standard_normal(4096) * 0.03
+    ref = 10.0 * np.log10(np.mean(x ** 2) / np.mean((dq - x) ** 2))
+    assert abs(oracle.snr_db(x, dq) - ref) < 1e-9
+    # scaling both by a constant changes nothing; doubling the noise amplitude costs 20 log10 2 dB
+    assert abs(oracle.snr_db(3.0 * x, 3.0 * dq) - ref) < 1e-9
+    assert abs(oracle.snr_db(x, x + 2.0 * (dq - x)) - (ref - 20.0 * math.log10(2.0))) < 1e-9

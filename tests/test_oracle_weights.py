@@ -1,7 +1,8 @@
-"""Pins for the oracle's weight path: AdamW (Sec. 2.2, Eq. 3) against a library
-optimizer, the closed form of the automatic scaling rule (Sec. 3.2, Eq. 6), the
+"""Pins for the oracle's weight path: AdamW (Sec. 2.2, Eq. 1) against a library
+optimizer, the closed form of the automatic scaling rule (Sec. 3.2, Eq. 10), the
 bound it rests on, interval re-scaling, restart equivalence and the cast."""
 import copy
+from fractions import Fraction
 
 import numpy as np
 import pytest
@@ -15,6 +16,12 @@ HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
 def args_for(oracle, step, **kw):
     hp = mi.adamw_hparams(step, **{**HP, **kw})
     return oracle.adamw_args(**hp)
+
+
+def exact_out_of_range(w, s):
+    """#{|w| > 448 s} in exact rational arithmetic (every float is a rational)."""
+    limit = 448 * Fraction(float(s))
+    return sum(1 for x in np.abs(w).ravel().tolist() if Fraction(x) > limit)
 
 
 def small_run(oracle, steps, rows=48, cols=96, interval=500, margin=1.0, sparse=False, on_step=None, lr=3e-4):
@@ -77,7 +84,7 @@ def test_single_spike_update_closed_form(oracle):
 
 
 def test_scale_prediction_closed_form(oracle):
-    # Eq. 6: s_t = s_0 + eta * t / 448
+    # Eq. 10: s_t = s_0 + eta * t / 448
     seen = []
 
     def on_step(t, w, st, wq, wq_t):
@@ -106,7 +113,10 @@ def test_predicted_scale_dominates_exact_scale_and_never_overflows(oracle, spars
         assert np.array_equal(wq_t, wq.T)
         ratios.append(float(st.s_cur) / float(s_jit))
     w, m, v, st, wq = small_run(oracle, 120, sparse=sparse, on_step=on_step)
-    assert st.overflow_count == 0
+    # no predicted scale let an element out of range; what the counter holds comes from the exact scale of
+    # the initialisation, which may sit one rounding of amax/448 below the largest element
+    assert st.overflow_count == exact_out_of_range(mi.config4_weights(48, 96, seed=4), st.s_base)
+    assert st.clipped_count == 0
     assert st.step == 120 and st.last_rebase == 0
     assert 1.0 <= min(ratios) and max(ratios) < 2.0   # curves stay close (Fig. 4)
 
@@ -144,18 +154,40 @@ def test_overflow_is_counted_and_saturated_when_the_bound_is_broken(oracle):
     m = np.zeros_like(w); v = np.zeros_like(w)
     st, _, _ = oracle.weight_init(w)
     total = 0
+    out_of_range = exact_out_of_range(w, st.s_cur)
     for t in range(1, 6):
         g = mi.config4_grad(t, rows, cols, seed=5)
         a = args_for(oracle, t, lr=1e-2, margin=1e-4)
         wq, _ = oracle.weight_step(w, m, v, g, a, st)
         y = w * (np.float32(1.0) / np.float32(st.s_cur))
         total += int((np.abs(y) > 464.0).sum())
+        out_of_range += exact_out_of_range(w, st.s_cur)
         assert ((wq & 0x7F) == 0x7E).sum() >= (np.abs(y) > 464.0).sum()
         # everything the count leaves out is what the library's unsaturated cast also maps to 448
         keep = np.abs(y) <= 464.0
         assert np.array_equal(wq[keep], torch.from_numpy(y[keep]).to(torch.float8_e4m3fn).view(torch.uint8).numpy())
         assert (wq & 0x7F).max() <= 0x7E
-    assert total > 0 and st.overflow_count == total
+    assert total > 0 and st.clipped_count == total
+    # the range test itself, |w| > 448 s_t, counted in exact rational arithmetic
+    assert st.overflow_count == out_of_range and out_of_range >= total
+
+
+def test_range_counter_at_the_exact_scale(oracle):
+    # s_0 = fl(amax / 448) can round below amax / 448: the largest elements are then (by less than one
+    # part in 2^24) outside 448 s_0 and are counted, although their codes are +-448 without any clipping.
+    below = above = 0
+    for k in range(400):
+        amax = np.float32(0.02 + k * 1.37e-5)
+        s = amax / np.float32(448.0)
+        w = np.full((2, 32), 0.25, np.float32) * amax
+        w[0, 3] = amax; w[1, 7] = -amax; w[1, 9] = np.nextafter(amax, np.float32(0))
+        st, wq, _ = oracle.weight_init(w)
+        assert st.s_base == s and st.clipped_count == 0
+        assert wq[0, 3] == 0x7E and wq[1, 7] == 0xFE
+        rounded_down = 448 * Fraction(float(s)) < Fraction(float(amax))
+        assert st.overflow_count == (2 if rounded_down else 0) == exact_out_of_range(w, s)
+        below += rounded_down; above += not rounded_down
+    assert below > 50 and above > 50          # both roundings occur in the sweep
 
 
 def test_restart_equivalence(oracle):
