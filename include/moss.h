@@ -51,7 +51,7 @@ int moss_device_cu_count(void);
 #define MOSS_DT_F32 1
 
 /* ---------------------------------------------------------------------------
- * Two-level microscaling quantizer  (paper Sec. 3.1, Eq. 1 and Eq. 2, and the
+ * Two-level microscaling quantizer  (paper Sec. 3.1, Eq. 2 and Eq. 3, and the
  * quantize / dequantize maps Q = round(X / (s ss_i)),  DQ = Q s ss_i).
  *
  *   x        BF16 [rows x cols], row stride `ld` elements.
@@ -100,7 +100,7 @@ int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_
  * serialised on one stream. */
 void moss_quant_set_poll_limit(unsigned polls);
 
-/* The same quantizer for a tensor whose producer already knows a bound of |X| (Sec. 3.1, Eq. 1:
+/* The same quantizer for a tensor whose producer already knows a bound of |X| (Sec. 3.1, Eq. 2:
  * the global scale is the largest of the group scales, s = max|X| / 448; a kernel that writes X can
  * keep the running maximum of what it writes, and the search for it, one extra pass over X, falls
  * away).
@@ -108,7 +108,7 @@ void moss_quant_set_poll_limit(unsigned polls);
  *                  value >= max|X| (what an unsigned atomic maximum over `bits & 0x7FFF` of every
  *                  element written leaves; moss_swiglu_bf16 below writes such a word).  With
  *                  exactly max|X| every output equals that of moss_quant_act_2level; with a larger
- *                  bound the outputs are Eq. 1-2 evaluated with the bound in place of max|X|; with
+ *                  bound the outputs are Eq. 2-3 evaluated with the bound in place of max|X|; with
  *                  a smaller value or a non-finite pattern the outputs are unspecified.
  * Everything else as above; no workspace; one launch, X is read once.                           */
 int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
@@ -141,22 +141,32 @@ int moss_swiglu_bf16_backward(const void *gate, const void *up, const void *dh, 
                               void *stream);
 
 /* ---------------------------------------------------------------------------
- * Per-tensor FP8 weights with automatic scaling  (paper Sec. 3.2, Eq. 6 and the
- * interval re-scaling of its last paragraph; AdamW as in Sec. 2.2 Eq. 3; App. C).
+ * Per-tensor FP8 weights with automatic scaling  (paper Sec. 3.2, Eq. 10 and the
+ * interval re-scaling of its last paragraph; AdamW as in Sec. 2.2 Eq. 1; App. C).
  *
  * The state is a small plain struct in DEVICE memory that the caller owns and may
  * copy out / back in to checkpoint a run.
  * ------------------------------------------------------------------------- */
 typedef struct {
     float s_base;            /* s_0: amax(W)/448 at the last max-reduction */
-    float s_cur;             /* s_t: scale of the latest cast (Eq. 6) */
+    float s_cur;             /* s_t: scale of the latest cast (Eq. 10) */
     double cum_lr;           /* sum of margin*lr since the last max-reduction ("eta t") */
     int64_t step;            /* optimizer steps taken */
     int64_t last_rebase;     /* step of the last max-reduction */
     float amax_seen;         /* amax of the weights at the latest cast (free by-product) */
-    uint32_t overflow_count; /* elements the saturating cast clipped: |w/s| > 464, i.e. beyond the
-                                values that round to 448 by themselves; cumulative */
+    uint32_t overflow_count; /* elements outside the range the scale covers, |w| > 448 s_cur (compared
+                                exactly), summed over all casts since the initialisation.  A predicted
+                                scale that holds its bound adds nothing; the exact scale fl(amax/448) of
+                                the initialisation or of a re-scaling step may round below amax/448,
+                                and then counts the largest elements although nothing is clipped */
+    uint32_t clipped_count;  /* elements whose code the saturating cast changed: |fl(w fl(1/s))| > 464,
+                                i.e. beyond the values that round to 448 by themselves; same sum */
+    uint32_t flags;          /* MOSS_WSTATE_* bits, sticky until the next initialisation */
 } moss_wscale_state;
+
+/* moss_weight_autoscale_cast was called with args->step != state.step + 1: the caller's step count,
+ * which decides when the scale is re-based, has drifted from the state's. */
+#define MOSS_WSTATE_STEP_MISMATCH 1u
 
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;
@@ -165,7 +175,9 @@ typedef struct {
     float margin;                           /* multiplies lr in the prediction; the paper's rule is 1 */
     int32_t interval;                       /* max-reduction every `interval` steps; <= 0: never */
     int64_t step;                           /* number t of the step this call performs (1-based);
-                                               must equal state.step + 1 */
+                                               must equal state.step + 1 (the state lives on the
+                                               device, so the call cannot check it: a mismatch sets
+                                               MOSS_WSTATE_STEP_MISMATCH in state.flags) */
 } moss_adamw_args;
 
 size_t moss_weight_workspace_bytes(int64_t rows, int64_t cols);

@@ -12,6 +12,7 @@ _lib = None
 MOSS_DT_BF16, MOSS_DT_F32 = 0, 1
 MOSS_Q_ROW, MOSS_Q_COL = 1, 2
 MOSS_EXP_NEAREST, MOSS_EXP_CEIL = 0, 4
+MOSS_WSTATE_STEP_MISMATCH = 1
 
 
 class MossError(RuntimeError):
@@ -21,7 +22,8 @@ class MossError(RuntimeError):
 class WScaleState(C.Structure):
     _fields_ = [("s_base", C.c_float), ("s_cur", C.c_float), ("cum_lr", C.c_double),
                 ("step", C.c_int64), ("last_rebase", C.c_int64),
-                ("amax_seen", C.c_float), ("overflow_count", C.c_uint32)]
+                ("amax_seen", C.c_float), ("overflow_count", C.c_uint32),
+                ("clipped_count", C.c_uint32), ("flags", C.c_uint32)]
 
 
 class AdamWArgs(C.Structure):

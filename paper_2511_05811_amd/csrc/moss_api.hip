@@ -1,18 +1,20 @@
 // Status strings and cached device properties of libmoss_hip.so.
+#include <atomic>
+
 #include "moss_internal.h"
 
-static int g_cu_count[64];
+static std::atomic<int> g_cu_count[64];   // per device, 0 = not asked yet; racing first calls store the same value
 
 int moss_internal_cu_count()
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (g_cu_count[dev] == 0) {
-        int n = 0;
+    int n = g_cu_count[dev].load();
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-        g_cu_count[dev] = n;
+        g_cu_count[dev].store(n);
     }
-    return g_cu_count[dev];
+    return n;
 }
 
 extern "C" int moss_device_cu_count(void) { return moss_internal_cu_count(); }

@@ -45,6 +45,7 @@
 // c ^ ((r >> 1) & 7): the 16 rows a quarter-wave reads with one 16-byte access then hit
 // 16 different 16-byte bank groups, and a wave-wide global->LDS load still writes 1 KiB
 // of consecutive LDS (8 rows) while each lane fetches the chunk that belongs there.
+#include <atomic>
 #include <type_traits>
 
 #include "moss_internal.h"
@@ -69,7 +70,7 @@ extern __shared__ __attribute__((aligned(1024))) uint8_t big_smem[];
 __device__ __forceinline__ void dma16(const uint8_t *base, uint32_t off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
+                 :: "v"(off), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()
@@ -502,18 +503,19 @@ int moss_internal_gemm_big(int64_t M, int64_t N, int64_t K, const uint8_t *a_q, 
                           const uint8_t *, const float *, void *, int, int64_t, int, int, int);
     static const Kern kerns[4] = {k_gemm_mx_big<false, 4>, k_gemm_mx_big<true, 4>, k_gemm_mx_big<false, 2>,
                                   k_gemm_mx_big<true, 2>};
-    static bool attr_done[64][4];            // the LDS size attribute is set once per device and kernel
+    static std::atomic<bool> attr_done[64][4];   // the LDS size attribute is set once per device and kernel (setting it
+                                                 // twice from racing threads is harmless: same value)
     const int which = (b_e ? 1 : 0) | (narrow ? 2 : 0);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOSS_ERR_HIP;
-    bool(&attr_set)[4] = attr_done[dev];
-    if (!attr_set[which]) {
+    std::atomic<bool>(&attr_set)[4] = attr_done[dev];
+    if (!attr_set[which].load()) {
         if (hipFuncSetAttribute((const void *)kerns[which], hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes) !=
             hipSuccess) {
             (void)hipGetLastError();
             return MOSS_ERR_UNSUPPORTED;
         }
-        attr_set[which] = true;
+        attr_set[which].store(true);
     }
     // persistent workgroups: one per compute unit (rounded down to a multiple of 8 so that the tiles
     // of a workgroup stay on one XCD), or one per tile if there are fewer tiles

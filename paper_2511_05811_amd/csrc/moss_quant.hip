@@ -1,4 +1,4 @@
-// Two-level microscaling quantizer for gfx950 (paper Sec. 3.1, Eq. 1-2).
+// Two-level microscaling quantizer for gfx950 (paper Sec. 3.1, Eq. 2-3).
 //
 // Codes can only be emitted once the maximum of the whole tensor is known (s = amax/448), so
 // every path sees X, agrees on the maximum, and then, per group of 32 values, derives the
@@ -144,7 +144,7 @@ __device__ __forceinline__ int local_exponent(uint32_t a_bits, const GlobalScale
 // 2^(-e) for e in [-127, 0] as an FP32 bit pattern
 __device__ __forceinline__ float pow2_neg(int e) { return __uint_as_float((uint32_t)(127 - e) << 23); }
 
-// The code of x in a group with exponent e is cast((x * 2^-e) * (1/s)) (Sec. 3.1, Eq. 1).  The
+// The code of x in a group with exponent e is cast((x * 2^-e) * (1/s)) (Sec. 3.1, Eq. 2).  The
 // first product is exact, so x * (2^-e * (1/s)) rounds to the same value whenever that
 // single factor is finite; it is not for groups of tiny nonzero values under a small
 // global maximum, which take the two-product form.  An all-zero group (e = -127) gets the

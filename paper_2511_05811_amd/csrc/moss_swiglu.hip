@@ -1,7 +1,7 @@
 // SwiGLU forward and backward in BF16, each output with the maximum of its magnitudes: the producer
 // in front of the quantizer of the down projection (forward) and of the gate / up projections' dY
 // (backward).  The paper keeps the non-linear layers in BF16 (Sec. 4.1); what this adds is the tensor
-// maximum of Sec. 3.1, Eq. 1 as a by-product of writing the tensor, so that the quantizer of these
+// maximum of Sec. 3.1, Eq. 2 as a by-product of writing the tensor, so that the quantizer of these
 // tensors (172 MiB each at LLaMA-7B sizes and 8192 tokens: too large to be kept on chip between a
 // search for the maximum and the conversion) reads them once.
 //

@@ -1,5 +1,5 @@
-// Per-tensor FP8 weights with automatic scaling for gfx950 (paper Sec. 3.2, Eq. 6;
-// AdamW of Sec. 2.2 Eq. 3; App. C).
+// Per-tensor FP8 weights with automatic scaling for gfx950 (paper Sec. 3.2, Eq. 10;
+// AdamW of Sec. 2.2 Eq. 1; App. C).
 //
 // The optimizer step is one streaming pass: each workgroup derives the predicted
 // scale s_t = s_base + cum_lr/448 from the device-resident state (O(1), no
@@ -22,8 +22,33 @@ constexpr float kClip = 464.0f;
 
 struct WPartials {
     float *amax;      // [slots]
-    uint32_t *over;   // [slots]
+    uint32_t *over;   // [slots] elements outside 448 s
+    uint32_t *clip;   // [slots] elements the saturation changed
 };
+
+// per-thread running by-products of a cast
+struct WCounts {
+    float amax = 0.0f;
+    uint32_t over = 0, clip = 0;
+};
+
+// The scale is meant to keep |w| / s within 448 (Sec. 3.2, text under Eq. 10); an element is out of
+// range when |w| > 448 s, compared exactly.  448 s has up to 27 significant bits, but for a single w
+// "w > 448 s" is the same as "w > the largest single that does not exceed 448 s", so one
+// double product per workgroup leaves a single-precision comparison per element.
+__device__ __forceinline__ float range_limit(float s)
+{
+    const double exact = 448.0 * (double)s;
+    float t = (float)exact;
+    if ((double)t > exact) t = __uint_as_float(__float_as_uint(t) - 1u);
+    return t;
+}
+
+__device__ __forceinline__ void count4(WCounts &c, const float4 &wv, float y0, float y1, float y2, float y3, float limit)
+{
+    c.over += (fabsf(wv.x) > limit) + (fabsf(wv.y) > limit) + (fabsf(wv.z) > limit) + (fabsf(wv.w) > limit);
+    c.clip += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
+}
 
 // one slot per workgroup of the largest grid a call may launch
 __host__ __device__ inline int64_t partial_slots(int64_t rows, int64_t cols)
@@ -37,37 +62,42 @@ __device__ __forceinline__ WPartials ws_partials(void *ws, int64_t slots)
     WPartials p;
     p.amax = reinterpret_cast<float *>(ws);
     p.over = reinterpret_cast<uint32_t *>(ws) + slots;
+    p.clip = reinterpret_cast<uint32_t *>(ws) + 2 * slots;
     return p;
 }
 
-// Block-wide max / sum; the result is valid in thread 0 only.
-__device__ __forceinline__ void block_reduce(float &amax, uint32_t &over)
+// Block-wide max / sums; the result is valid in thread 0 only.
+__device__ __forceinline__ void block_reduce(WCounts &c)
 {
     __shared__ float r_amax[kWThreads / kWave];
-    __shared__ uint32_t r_over[kWThreads / kWave];
-    amax = wave_max_f32(amax);
-    over = wave_sum_u32(over);
+    __shared__ uint32_t r_over[kWThreads / kWave], r_clip[kWThreads / kWave];
+    c.amax = wave_max_f32(c.amax);
+    c.over = wave_sum_u32(c.over);
+    c.clip = wave_sum_u32(c.clip);
     if ((threadIdx.x & 63) == 0) {
-        r_amax[threadIdx.x >> 6] = amax;
-        r_over[threadIdx.x >> 6] = over;
+        r_amax[threadIdx.x >> 6] = c.amax;
+        r_over[threadIdx.x >> 6] = c.over;
+        r_clip[threadIdx.x >> 6] = c.clip;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 1; i < kWThreads / kWave; i++) {
-            amax = fmaxf(amax, r_amax[i]);
-            over += r_over[i];
+            c.amax = fmaxf(c.amax, r_amax[i]);
+            c.over += r_over[i];
+            c.clip += r_clip[i];
         }
     }
 }
 
-__device__ __forceinline__ void block_reduce_store(float amax, uint32_t over, void *ws, int64_t slots)
+__device__ __forceinline__ void block_reduce_store(WCounts c, void *ws, int64_t slots)
 {
-    block_reduce(amax, over);
+    block_reduce(c);
     if (threadIdx.x == 0) {
         WPartials p = ws_partials(ws, slots);
         const int64_t b = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-        p.amax[b] = amax;
-        p.over[b] = over;
+        p.amax[b] = c.amax;
+        p.over[b] = c.over;
+        p.clip[b] = c.clip;
     }
 }
 
@@ -86,7 +116,7 @@ struct AdamW {
 };
 
 // One AdamW element update; every operation is a single correctly rounded FP32
-// operation in the order of Eq. 3 of the paper (no FMA contraction; the build asks for
+// operation in the order of Eq. 1 of the paper (no FMA contraction; the build asks for
 // IEEE division and square root).
 __device__ __forceinline__ void adamw_elem(float &w, float &m, float &v, float g, const AdamW &a)
 {
@@ -102,7 +132,7 @@ __device__ __forceinline__ void adamw_elem(float &w, float &m, float &v, float g
     v = vi;
 }
 
-// Scale the cast of this call uses.  predict != 0: Eq. 6 from the state before the
+// Scale the cast of this call uses.  predict != 0: Eq. 10 from the state before the
 // step; predict == 0: the scale already stored in the state (after init / re-base).
 __device__ __forceinline__ float scale_for_cast(const moss_wscale_state *st, int predict, double lr_term)
 {
@@ -118,13 +148,13 @@ __global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w,
                                                           const moss_wscale_state *__restrict__ st,
                                                           uint8_t *__restrict__ wq, void *ws, int64_t slots)
 {
-    float inv_s = 0.0f;
+    float inv_s = 0.0f, limit = 0.0f;
     if (DO_CAST) {
         float s = scale_for_cast(st, 1, lr_term);
         inv_s = s > 0.0f ? 1.0f / s : 0.0f;
+        limit = range_limit(s);
     }
-    float amax = 0.0f;
-    uint32_t over = 0;
+    WCounts cnt;
     const int64_t stride = (int64_t)gridDim.x * kWThreads;
     for (int64_t i = (int64_t)blockIdx.x * kWThreads + threadIdx.x; i < n4; i += stride) {
         float4 wv = ld_stream_f4(reinterpret_cast<float4 *>(w) + i);
@@ -138,26 +168,26 @@ __global__ __launch_bounds__(kWThreads) void k_adamw_cast(float *__restrict__ w,
         st_stream_f4(reinterpret_cast<float4 *>(w) + i, wv);
         st_stream_f4(reinterpret_cast<float4 *>(m) + i, mv);
         st_stream_f4(reinterpret_cast<float4 *>(v) + i, vv);
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+        cnt.amax = fmaxf(cnt.amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
         if (DO_CAST) {
             float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
-            over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
+            count4(cnt, wv, y0, y1, y2, y3, limit);
             st_stream4(reinterpret_cast<uint32_t *>(wq) + i, cvt4_e4m3_sat(y0, y1, y2, y3));
         }
     }
-    block_reduce_store(amax, over, ws, slots);
+    block_reduce_store(cnt, ws, slots);
 }
 
 template <bool W_BF16>
 __global__ __launch_bounds__(kWThreads) void k_weight_amax(const void *__restrict__ w, int64_t n4, void *ws, int64_t slots)
 {
-    float amax = 0.0f;
+    WCounts cnt;
     const int64_t stride = (int64_t)gridDim.x * kWThreads;
     for (int64_t i = (int64_t)blockIdx.x * kWThreads + threadIdx.x; i < n4; i += stride) {
         float4 wv = load_as_f32x4(w, i, W_BF16);
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+        cnt.amax = fmaxf(cnt.amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
     }
-    block_reduce_store(amax, 0u, ws, slots);
+    block_reduce_store(cnt, ws, slots);
 }
 
 template <bool W_BF16>
@@ -167,17 +197,17 @@ __global__ __launch_bounds__(kWThreads) void k_weight_cast(const void *__restric
 {
     const float s = scale_for_cast(st, 0, 0.0);
     const float inv_s = s > 0.0f ? 1.0f / s : 0.0f;
-    float amax = 0.0f;
-    uint32_t over = 0;
+    const float limit = range_limit(s);
+    WCounts cnt;
     const int64_t stride = (int64_t)gridDim.x * kWThreads;
     for (int64_t i = (int64_t)blockIdx.x * kWThreads + threadIdx.x; i < n4; i += stride) {
         float4 wv = load_as_f32x4(w, i, W_BF16);
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+        cnt.amax = fmaxf(cnt.amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
         float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
-        over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
+        count4(cnt, wv, y0, y1, y2, y3, limit);
         st_stream4(reinterpret_cast<uint32_t *>(wq) + i, cvt4_e4m3_sat(y0, y1, y2, y3));
     }
-    block_reduce_store(amax, over, ws, slots);
+    block_reduce_store(cnt, ws, slots);
 }
 
 // 2-D variant used when the transposed codes are wanted as well: a workgroup owns a
@@ -197,11 +227,11 @@ __global__ __launch_bounds__(kWThreads) void k_weight_tile(float *__restrict__ w
     __shared__ __attribute__((aligned(16))) uint8_t tt[kWTile][kPitch];   // [column][row]
     const float s = scale_for_cast(st, STEP ? 1 : 0, lr_term);
     const float inv_s = s > 0.0f ? 1.0f / s : 0.0f;
+    const float limit = range_limit(s);
     const int tid = threadIdx.x, rl = tid >> 5, c4 = (tid & 31) * 4;
     const int64_t r0 = (int64_t)blockIdx.y * kWTile, c0 = (int64_t)blockIdx.x * kWTile;
     const int64_t col = c0 + c4;
-    float amax = 0.0f;
-    uint32_t over = 0;
+    WCounts cnt;
 #pragma unroll 4
     for (int it = 0; it < 16; it++) {
         const int rr = it * 8 + rl;
@@ -225,9 +255,9 @@ __global__ __launch_bounds__(kWThreads) void k_weight_tile(float *__restrict__ w
             } else {
                 wv = load_as_f32x4(src, i4, SRC_BF16);
             }
-            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
+            cnt.amax = fmaxf(cnt.amax, fmaxf(fmaxf(fabsf(wv.x), fabsf(wv.y)), fmaxf(fabsf(wv.z), fabsf(wv.w))));
             const float y0 = wv.x * inv_s, y1 = wv.y * inv_s, y2 = wv.z * inv_s, y3 = wv.w * inv_s;
-            over += (fabsf(y0) > kClip) + (fabsf(y1) > kClip) + (fabsf(y2) > kClip) + (fabsf(y3) > kClip);
+            count4(cnt, wv, y0, y1, y2, y3, limit);
             code = cvt4_e4m3_sat(y0, y1, y2, y3);
             st_stream4(reinterpret_cast<uint32_t *>(wq) + i4, code);
         }
@@ -245,7 +275,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_tile(float *__restrict__ w
             st_stream16(wq_t + (c0 + c) * rows + r0 + piece * 16, make_uint4(p[0], p[1], p[2], p[3]));
         }
     }
-    block_reduce_store(amax, over, ws, slots);
+    block_reduce_store(cnt, ws, slots);
 }
 
 enum FinalizeMode {
@@ -255,18 +285,23 @@ enum FinalizeMode {
     kFinCastOnly = 3  // after a cast-only pass: record amax, add overflow
 };
 
+// `step`: the step number the caller says this call performs (only looked at by the two modes that
+// advance the step count): a caller whose count has drifted from the state's is flagged in the state.
 __global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state *st, void *ws, int64_t slots,
-                                                               int n_partial, int mode, double lr_term)
+                                                               int n_partial, int mode, double lr_term, int64_t step)
 {
     WPartials p = ws_partials(ws, slots);
-    float amax = 0.0f;
-    uint32_t over = 0;
+    WCounts c;
     for (int i = threadIdx.x; i < n_partial; i += kWThreads) {
-        amax = fmaxf(amax, p.amax[i]);
-        over += p.over[i];
+        c.amax = fmaxf(c.amax, p.amax[i]);
+        c.over += p.over[i];
+        c.clip += p.clip[i];
     }
-    block_reduce(amax, over);
+    block_reduce(c);
     if (threadIdx.x != 0) return;
+    const float amax = c.amax;
+    const uint32_t over = c.over, clip = c.clip;
+    if ((mode == kFinStep || mode == kFinRebase) && st->step + 1 != step) st->flags |= MOSS_WSTATE_STEP_MISMATCH;
     if (mode == kFinInit) {
         st->s_base = amax / kE4M3Max;
         st->s_cur = st->s_base;
@@ -275,6 +310,8 @@ __global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state
         st->last_rebase = 0;
         st->amax_seen = amax;
         st->overflow_count = 0;
+        st->clipped_count = 0;
+        st->flags = 0;
     } else if (mode == kFinStep) {
         double cum = st->cum_lr + lr_term;
         st->cum_lr = cum;
@@ -282,6 +319,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state
         st->step += 1;
         st->amax_seen = amax;
         st->overflow_count += over;
+        st->clipped_count += clip;
     } else if (mode == kFinRebase) {
         st->step += 1;
         st->s_base = amax / kE4M3Max;
@@ -292,6 +330,7 @@ __global__ __launch_bounds__(kWThreads) void k_weight_finalize(moss_wscale_state
     } else {
         st->amax_seen = amax;
         st->overflow_count += over;
+        st->clipped_count += clip;
     }
 }
 
@@ -335,7 +374,7 @@ static int launch_transpose(const uint8_t *src, int64_t rows, int64_t cols, uint
 extern "C" size_t moss_weight_workspace_bytes(int64_t rows, int64_t cols)
 {
     if (rows <= 0 || cols <= 0) return 0;
-    return (size_t)moss::partial_slots(rows, cols) * (sizeof(float) + sizeof(uint32_t));
+    return (size_t)moss::partial_slots(rows, cols) * (sizeof(float) + 2 * sizeof(uint32_t));
 }
 
 static int check_weight_common(int64_t rows, int64_t cols, const void *state, const void *wq, const void *wq_t,
@@ -364,9 +403,10 @@ struct WLaunch {
     moss_wscale_state *state;
 };
 
-static int finalize(const WLaunch &L, int n_partial, int mode, double lr_term)
+static int finalize(const WLaunch &L, int n_partial, int mode, double lr_term, int64_t step = 0)
 {
-    hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, L.st, L.state, L.ws, L.slots, n_partial, mode, lr_term);
+    hipLaunchKernelGGL(k_weight_finalize, dim3(1), dim3(kWThreads), 0, L.st, L.state, L.ws, L.slots, n_partial, mode, lr_term,
+                       step);
     MOSS_LAUNCH_CHECK();
     return MOSS_OK;
 }
@@ -461,7 +501,7 @@ extern "C" int moss_weight_autoscale_cast(float *w, float *m, float *v, const vo
         else
             hipLaunchKernelGGL((k_adamw_cast<false, false>), g1, blk, 0, L.st, w, m, v, g, L.n4, a, lr_term, state, wq, workspace, L.slots);
         MOSS_LAUNCH_CHECK();
-        if ((rc = finalize(L, L.grid1d, kFinRebase, lr_term))) return rc;
+        if ((rc = finalize(L, L.grid1d, kFinRebase, lr_term, args->step))) return rc;
         return cast_only(L, w, false, wq, wq_t);
     }
     if (wq_t && tile_path_ok(rows, cols)) {
@@ -470,14 +510,14 @@ extern "C" int moss_weight_autoscale_cast(float *w, float *m, float *v, const vo
         else
             hipLaunchKernelGGL((k_weight_tile<true, false>), L.grid2d, blk, 0, L.st, w, m, v, g, rows, cols, a, lr_term, state, wq, wq_t, workspace, L.slots);
         MOSS_LAUNCH_CHECK();
-        return finalize(L, (int)(L.grid2d.x * L.grid2d.y), kFinStep, lr_term);
+        return finalize(L, (int)(L.grid2d.x * L.grid2d.y), kFinStep, lr_term, args->step);
     }
     if (gb)
         hipLaunchKernelGGL((k_adamw_cast<true, true>), g1, blk, 0, L.st, w, m, v, g, L.n4, a, lr_term, state, wq, workspace, L.slots);
     else
         hipLaunchKernelGGL((k_adamw_cast<false, true>), g1, blk, 0, L.st, w, m, v, g, L.n4, a, lr_term, state, wq, workspace, L.slots);
     MOSS_LAUNCH_CHECK();
-    if ((rc = finalize(L, L.grid1d, kFinStep, lr_term))) return rc;
+    if ((rc = finalize(L, L.grid1d, kFinStep, lr_term, args->step))) return rc;
     if (wq_t) return launch_transpose(wq, rows, cols, wq_t, L.st);
     return MOSS_OK;
 }

@@ -4,11 +4,11 @@
     python -m paper_2511_05811_amd.microbench scaling   # Table "Time usage to calculate per-tensor scaling factors" (Sec. 3.2)
                                                          # and the interval sweep of the scaling ablation (App.)
     python -m paper_2511_05811_amd.microbench gemm      # Table "Runtime of quantized FP8 GEMM" (Sec. 4.3): its seven shapes
-    python -m paper_2511_05811_amd.microbench snr       # Sec. 3.1 Eq. 3 / SNR table: per-tensor vs two-level microscaling
+    python -m paper_2511_05811_amd.microbench snr       # Sec. 3.1 Eq. 4 / SNR table: per-tensor vs two-level microscaling
     python -m paper_2511_05811_amd.microbench block     # Sec. 4 setting, one decoder block: tokens/s with the linears on the
                                                          # FP8 path vs BF16 GEMMs (attention, norms, SwiGLU: BF16 torch ops)
     python -m paper_2511_05811_amd.microbench producer  # SwiGLU that also hands the tensor maximum to the quantizer (Sec. 3.1,
-                                                         # Eq. 1 without the search): one pass over h instead of two
+                                                         # Eq. 2 without the search): one pass over h instead of two
     python -m paper_2511_05811_amd.microbench limits    # what the machine allows: GEMM rate and shader clock by operand
                                                          # content (power limit), plain device-copy bandwidth
 
@@ -115,7 +115,7 @@ def scaling(moss, torch, small=False):
             moss.weight_autoscale_cast(w, m, v, g, _adamw_args(moss, tt[0], iv), state, wq=wq, workspace=ws)
 
         extra = _time_ms(torch, lambda: one_more(1), 6)[0] - _time_ms(torch, lambda: one_more(0), 6)[0]
-        sweep.append({"interval": interval, "steps": steps, "overflow_count": int(st.overflow_count),
+        sweep.append({"interval": interval, "steps": steps, "clipped_count": int(st.clipped_count), "out_of_range_count": int(st.overflow_count),
                       "min_predicted_over_exact_scale": round(worst, 4),
                       "amortised_max_reduction_ms_per_step": round(extra / interval, 5)})
         del w, m, v, wq
@@ -161,7 +161,7 @@ def _e4m3_table(torch, dev):
 
 
 def snr(moss, torch, small=False):
-    """SNR = 10 log10(sum x^2 / sum (x - DQ(Q(x)))^2) (Sec. 3.1, Eq. 3) of the library's codes on
+    """SNR = 10 log10(sum x^2 / sum (x - DQ(Q(x)))^2) (Sec. 3.1, Eq. 4) of the library's codes on
     heavy-tailed activations with outlier channels; the per-tensor row uses the library's
     per-tensor cast (the weight path's initialisation) on the same tensor."""
     dev = torch.device("cuda:0")
@@ -214,7 +214,7 @@ def snr(moss, torch, small=False):
     return {"table": "snr", "unit": "dB", "shape": [rows, cols], "snr": out,
             "note": "paper (activations of a trained 7B model): two-level 3.0-3.4 dB above per-group-128, 9.2-9.4 dB above per-tensor; "
                     "synthetic heavy-tailed tensors stand in, so only the ordering is comparable.  moss_nearest rounds the local exponent "
-                    "to the closest power of two as Eq. 2 prints it, which lets a group maximum exceed 448 by up to sqrt(2) and "
+                    "to the closest power of two as Eq. 3 prints it, which lets a group maximum exceed 448 by up to sqrt(2) and "
                     "saturate; moss_ceil rounds it up and never clips.  per_group_128_fp32_scales is a comparator computed with torch "
                     "operations; its whole-tensor figure is flattered by the outlier channels, which carry most of the power and, being "
                     "their groups' maxima, are represented exactly: compare the non-outlier columns"}

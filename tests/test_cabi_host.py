@@ -20,8 +20,9 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_struct_layouts_match_header():
-    assert C.sizeof(moss.WScaleState) == 40
+    assert C.sizeof(moss.WScaleState) == 48
     assert moss.WScaleState.cum_lr.offset == 8 and moss.WScaleState.overflow_count.offset == 36
+    assert moss.WScaleState.flags.offset == 44
     assert C.sizeof(moss.AdamWArgs) == 56 and moss.AdamWArgs.step.offset == 48
 
 

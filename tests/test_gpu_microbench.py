@@ -16,7 +16,7 @@ def test_scaling_table_small():
     row = res["sizes"][0]
     assert row["fused_step_auto_ms"] > 0 and row["step_with_max_reduction_ms"] > 0
     for s in res["interval_sweep"]:
-        assert s["overflow_count"] == 0
+        assert s["clipped_count"] == 0
         assert s["min_predicted_over_exact_scale"] >= 1.0   # the predicted scale never falls below the exact one
 
 
@@ -31,7 +31,7 @@ def test_snr_table_small():
     assert res["moss_ceil"] >= res["per_tensor"] - 1e-6
     # outlier channels dominate a per-tensor scale: the other channels gain most from local scales
     assert res["moss_ceil_non_outlier_channels"] >= res["per_tensor_non_outlier_channels"] - 1e-6
-    # rounding the exponent to the nearest power of two (Eq. 2 as printed) clips group maxima by up
+    # rounding the exponent to the nearest power of two (Eq. 3 as printed) clips group maxima by up
     # to sqrt(2): its SNR is reported, not asserted
     assert res["moss_nearest"] > 10.0
 

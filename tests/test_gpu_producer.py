@@ -1,5 +1,5 @@
 """GPU parity of the producer side of the quantizer: moss_swiglu_bf16 (+ backward) against the CPU
-oracle's FP64 SwiGLU, and moss_quant_act_2level_given_max (the quantizer of Sec. 3.1, Eq. 1-2 with
+oracle's FP64 SwiGLU, and moss_quant_act_2level_given_max (the quantizer of Sec. 3.1, Eq. 2-3 with
 the tensor maximum handed in) bit for bit against the oracle.
 
 SwiGLU tolerance: the kernel evaluates in FP32 with hardware exp2 / reciprocal approximations and

@@ -1,5 +1,5 @@
 """GPU parity of moss_quant_act_2level against the CPU oracle: bit-exact codes,
-exponent bytes and global scale (paper Sec. 3.1, Eq. 1-2)."""
+exponent bytes and global scale (paper Sec. 3.1, Eq. 2-3)."""
 import numpy as np
 import pytest
 import torch
