@@ -87,6 +87,19 @@ int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_
                           uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
                           float *s_global, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same call for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch (partial maxima, meeting
+ * words) lives in a 16 KiB array in the library's device data segment, one copy per GPU, held until the
+ * process ends; the call allocates nothing and frees nothing.  Arguments, outputs and errors as for
+ * moss_quant_act_2level; MOSS_ERR_WORKSPACE if a shape ever needed more scratch than the array holds
+ * (the quantizer's scratch does not grow with the shape, so every accepted shape fits); MOSS_ERR_HIP
+ * if the array's address cannot be resolved.  The first call on a device resolves that address (a host
+ * query, make it outside a capture).  All calls on one GPU share the one array: calls that overlap on a
+ * GPU (different streams, different threads) race; order them on one stream.                      */
+int moss_quant_act_2level_noalloc(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                                  uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
+                                  float *s_global, void *stream);
+
 /* Mid-sized and large tensors are quantized by one launch whose workgroups meet once, through
  * a few words of the workspace, to agree on the global maximum (Sec. 3.1: one FP32 scale per
  * tensor).  A workgroup polls for the result at most `polls` times before it computes the

@@ -60,6 +60,7 @@ def load():
     L.moss_quant_workspace_bytes.restype = sz
     L.moss_quant_workspace_bytes.argtypes = [i64, i64, u32]
     L.moss_quant_act_2level.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moss_quant_act_2level_noalloc.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp]
     L.moss_quant_act_2level_given_max.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp, vp]
     L.moss_swiglu_bf16.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
     L.moss_swiglu_bf16_backward.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp]
@@ -131,6 +132,19 @@ def quant_act_2level(x, flags=MOSS_Q_ROW, out=None, workspace=None):
                                  _ptr(s), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "moss_quant_act_2level")
     return dict(q_row=q_row, e_row=e_row, q_col=q_col, e_col=e_col, s=s)
+
+
+def quant_act_2level_noalloc(x, flags, out):
+    """moss_quant_act_2level_noalloc: every output tensor comes from the caller (`out` holds q_row/e_row and/or
+    q_col/e_col and s), the scratch is the library's own static array; nothing is allocated."""
+    rows, cols = x.shape
+    want_row, want_col = bool(flags & MOSS_Q_ROW), bool(flags & MOSS_Q_COL)
+    rc = load().moss_quant_act_2level_noalloc(
+        _ptr(x), rows, cols, x.stride(0), flags, _ptr(out["q_row"] if want_row else None),
+        _ptr(out["e_row"] if want_row else None), _ptr(out["q_col"] if want_col else None),
+        _ptr(out["e_col"] if want_col else None), _ptr(out["s"]), _stream())
+    _check(rc, "moss_quant_act_2level_noalloc")
+    return out
 
 
 def quant_act_2level_given_max(x, absmax_bits, flags=MOSS_Q_ROW, out=None):

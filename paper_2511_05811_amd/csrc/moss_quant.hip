@@ -746,9 +746,11 @@ static int launch_codes(const uint16_t *x, int64_t rows, int64_t cols, int64_t l
     return MOSS_OK;
 }
 
-extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
-                                     uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
-                                     float *s_global, void *workspace, size_t workspace_bytes, void *stream)
+// moss_quant_act_2level with its scratch (partial maxima, then the meeting words of the one-launch kernel) at
+// `workspace`, wherever that memory comes from.
+static int quant_with_workspace(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                                uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
+                                float *s_global, void *workspace, size_t workspace_bytes, void *stream)
 {
     using namespace moss;
     const bool want_row = flags & MOSS_Q_ROW, want_col = flags & MOSS_Q_COL, ceil_mode = flags & MOSS_EXP_CEIL;
@@ -801,6 +803,63 @@ extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t c
 
     return launch_codes(x, rows, cols, ld, want_row, want_col, ceil_mode, partial, n_partial, q_row, e_row, q_col, e_col,
                         s_global, st);
+}
+
+extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                                     uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
+                                     float *s_global, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, workspace,
+                                workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The entry point for callers that cannot allocate.  Its scratch is an array in the library's own
+// device data segment: every GPU the library runs on holds a copy (16 KiB, until the process ends) at an
+// address of its own, which the host learns once per device from hipGetSymbolAddress.  In host code the
+// array's name is only a handle for that query, never an address to hand to a kernel.
+namespace {
+
+constexpr size_t kScratchBytes = 16 * 1024;
+static __device__ __align__(256) uint8_t scratch[kScratchBytes];
+
+std::atomic<void *> g_scratch_ptr[64];   // per device: where that device's copy of `scratch` lives
+
+// Address of the current device's copy of the array (asked for on the first call on that device).
+int scratch_of_current_device(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return MOSS_ERR_HIP;
+    }
+    void *p = g_scratch_ptr[dev].load();
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return MOSS_ERR_HIP;
+        }
+        g_scratch_ptr[dev].store(p);   // racing first calls store the same address
+    }
+    *out = p;
+    return MOSS_OK;
+}
+
+}  // namespace
+
+extern "C" int moss_quant_act_2level_noalloc(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                                             uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
+                                             float *s_global, void *stream)
+{
+    // the scratch a shape needs must fit the array (today it does not grow with the shape, so this only
+    // fails if the two ever drift apart)
+    if (moss_quant_workspace_bytes(rows, cols, flags) > kScratchBytes) return MOSS_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const int rc = scratch_of_current_device(&ws);
+    if (rc != MOSS_OK) return rc;
+    // nothing in the array has to start at a known value: the partial maxima are written before they are
+    // read, and the one-launch path clears its meeting words with a kernel of its own on the same stream
+    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, ws, kScratchBytes, stream);
 }
 
 extern "C" int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
