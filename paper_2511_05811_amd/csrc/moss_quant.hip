@@ -85,11 +85,19 @@ struct GlobalScale {
     float frac;       // amax = frac * 2^expo, frac in [0.5, 1)
     int expo;
     bool zero;
+    // Integer form of the local exponent, for a tensor maximum that is a normal BF16 number (see fast_group)
+    bool fast;
+    int add;          // added to a group maximum's bit pattern before its exponent field is read
+    int ebase;        // 127 - exponent field of the tensor maximum
+    uint32_t fbits;   // bit pattern of inv_s with 127 added to its exponent field (may leave the finite range)
+    int wide_at;      // groups whose byte is <= wide_at need the two-product form (-1 or less: none)
 };
 
+template <bool CEIL>
 __device__ __forceinline__ GlobalScale make_global_scale(uint32_t amax_bits);
 
 // Every workgroup folds the (few) partial maxima itself: cheaper than another launch.
+template <bool CEIL>
 __device__ __forceinline__ GlobalScale fold_global_scale(const uint32_t *partial, int n_partial, uint32_t *red)
 {
     uint32_t m = 0;
@@ -103,11 +111,24 @@ __device__ __forceinline__ GlobalScale fold_global_scale(const uint32_t *partial
     const int nw = blockDim.x >> 6;
     m = red[0];
     for (int i = 1; i < nw; i++) m = red[i] > m ? red[i] : m;
-    return make_global_scale(m);
+    return make_global_scale<CEIL>(m);
 }
 
+// The exponent of a group with maximum a under the tensor maximum A is round(log2(a / A)) (Eq. 3), or
+// its ceiling.  For normal BF16 numbers a = 2^(Ea-127) (128 + ma) / 128, A likewise, so it is
+// Ea - EA + c with c in {-1, 0, +1} decided by the 7-bit mantissas alone:
+//   nearest: +1 iff (128 + ma)^2 >= 2 (128 + mA)^2,  -1 iff 2 (128 + ma)^2 < (128 + mA)^2
+//            (for a given mA only one of the two can happen: the first for mA <= 52, the second for mA >= 54);
+//   ceiling: +1 iff ma > mA.
+// Either way c = +1 is "ma >= some threshold T", c = -1 is "ma < T": adding 128 - T (or -T) to the 15-bit
+// pattern of a carries into (borrows from) its exponent field exactly when c applies, and
+//   Ea - EA + c = ((a + add) >> 7) - EA
+// with one constant per tensor.  Zero groups and groups whose maximum is a BF16 subnormal do not fit this
+// form and are handled apart.
+template <bool CEIL>
 __device__ __forceinline__ GlobalScale make_global_scale(uint32_t m)
 {
+    m = (uint32_t)__builtin_amdgcn_readfirstlane((int)m);   // the same in every lane: keep what follows in scalar registers
     GlobalScale g;
     float amax = bf16_bits_to_f32(m);
     g.zero = (m == 0);
@@ -115,11 +136,46 @@ __device__ __forceinline__ GlobalScale make_global_scale(uint32_t m)
     g.inv_s = fminf(1.0f / g.s, __FLT_MAX__);   // finite, so that zero inputs keep code zero
     g.frac = __builtin_amdgcn_frexp_mantf(amax);
     g.expo = __builtin_amdgcn_frexp_expf(amax);
+    const int mA = (int)(m & 127u), EA = (int)(m >> 7), M = 128 + mA;
+    g.fast = EA >= 1;
+    if (CEIL) {
+        g.add = 127 - mA;
+    } else {
+        int t = (int)((float)M * 1.41421356f);               // ceil(sqrt(2) M), fixed up in integers
+        while (t * t < 2 * M * M) t++;
+        while ((t - 1) * (t - 1) >= 2 * M * M) t--;
+        if (t <= 255) {
+            g.add = 256 - t;                                   // +1 iff 128 + ma >= t
+        } else {
+            int u = (int)((float)M * 0.70710678f);             // ceil(M / sqrt(2))
+            while (2 * u * u < M * M) u++;
+            while (2 * (u - 1) * (u - 1) >= M * M) u--;
+            g.add = 128 - u;                                   // -1 iff 128 + ma < u
+        }
+    }
+    g.ebase = 127 - EA;
+    const uint32_t ib = __float_as_uint(g.inv_s);
+    g.fbits = ib + (127u << 23);
+    g.wide_at = (int)(ib >> 23) - 128;
     return g;
 }
 
-// e = round(log2(a/amax)) (or its ceiling), clamped to [-127, 0]; a = 15-bit BF16
-// magnitude bits.  With a = f_a 2^ea and amax = f_A 2^eA (f in [0.5,1), at most 8
+// Exponent byte and factor 2^-e * (1/s) of a group with maximum bit pattern a (zero or a normal number) in
+// the integer form: 2^-e * (1/s) is inv_s with -e added to its exponent field (finite unless byte <= g.wide_at,
+// which the caller checks through min_fbyte).  A zero group stores byte 0 and multiplies its zeros by 1/s.
+__device__ __forceinline__ void fast_group(uint32_t a, const GlobalScale &g, uint32_t &byte, float &factor, uint32_t &min_fbyte)
+{
+    int k = (int)((a + (uint32_t)g.add) >> 7) + g.ebase;
+    k = k < 0 ? 0 : k;
+    const bool z = a == 0;
+    byte = z ? 0u : (uint32_t)k;
+    const uint32_t fb = z ? 127u : (uint32_t)k;
+    min_fbyte = fb < min_fbyte ? fb : min_fbyte;
+    factor = __uint_as_float(g.fbits - (fb << 23));
+}
+
+// The general form (any finite a, any tensor maximum): e = round(log2(a/amax)) (or its ceiling), clamped
+// to [-127, 0]; a = 15-bit BF16 magnitude bits.  With a = f_a 2^ea and amax = f_A 2^eA (f in [0.5,1), at most 8
 // significant bits) the candidates are ea-eA-1, ea-eA, ea-eA+1 and the choice needs
 // only products of two 8-bit significands, exact in FP32:
 //   nearest: +1 if f_a^2 >= 2 f_A^2, -1 if 2 f_a^2 < f_A^2;   ceil: +1 if f_a > f_A.
@@ -166,7 +222,24 @@ __device__ __forceinline__ float scaled(float x, float fused, uint32_t ebyte, fl
     return FUSED ? x * fused : (x * pow2_neg_of_byte(ebyte)) * inv_s;
 }
 
-__device__ __forceinline__ float clamp448(float y) { return __builtin_amdgcn_fmed3f(y, kE4M3Max, -kE4M3Max); }
+// Saturation of the cast.  The converter turns values beyond +-448 into the NaN code unless the wave's
+// FP16_OVFL mode bit is set, in which case it saturates to the largest finite code by itself: the kernels
+// set the bit once (converter_saturates) instead of clamping every value first (one instruction per value
+// and grouping saved; the exhaustive all-BF16-values test covers the behaviour).  The mode bit lives and dies
+// with the wave, and these kernels have no other instruction that it affects.
+__device__ __forceinline__ float clamp448(float y) { return y; }
+__device__ __forceinline__ void converter_saturates()
+{
+    __builtin_amdgcn_s_setreg((1 - 1) << 11 | 23 << 6 | 1, 1);   // hwreg(MODE, offset 23, 1 bit) = 1
+}
+
+// four FP32 values -> four E4M3 bytes (a in the lowest byte), saturating
+__device__ __forceinline__ uint32_t cvt4_sat(float a, float b, float c, float d)
+{
+    int r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a), clamp448(b), 0, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(c), clamp448(d), r, true);
+    return (uint32_t)r;
+}
 
 __device__ __forceinline__ uint32_t quad_max_u32(uint32_t v)
 {
@@ -188,7 +261,7 @@ __device__ __forceinline__ uint2 row_codes(const uint4 &r, float fused, uint32_t
         const float y1 = scaled<FUSED>(__uint_as_float(w[2 * h] & 0xFFFF0000u), fused, ebyte, inv_s);
         const float y2 = scaled<FUSED>(bf16_bits_to_f32(w[2 * h + 1] & 0xFFFFu), fused, ebyte, inv_s);
         const float y3 = scaled<FUSED>(__uint_as_float(w[2 * h + 1] & 0xFFFF0000u), fused, ebyte, inv_s);
-        out[h] = cvt4_e4m3_sat(y0, y1, y2, y3);
+        out[h] = cvt4_sat(y0, y1, y2, y3);
     }
     return make_uint2(out[0], out[1]);
 }
@@ -206,7 +279,8 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
                                                              float *__restrict__ s_global)
 {
     __shared__ uint32_t red[kQuantThreads / kWave];
-    const GlobalScale g = fold_global_scale(partial, n_partial, red);
+    converter_saturates();
+    const GlobalScale g = fold_global_scale<CEIL>(partial, n_partial, red);
     if (blockIdx.x == 0 && threadIdx.x == 0) *s_global = g.s;
 
     const int64_t base = (int64_t)blockIdx.x * (kQuantThreads * kRowUnroll) + threadIdx.x;
@@ -227,18 +301,28 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
         }
     }
     float f[kRowUnroll];
-    uint32_t eb[kRowUnroll];
-    bool wide = false;
+    uint32_t eb[kRowUnroll], gmax[kRowUnroll];
+    uint32_t sub_min = ~0u, min_fb = 255u;
 #pragma unroll
     for (int u = 0; u < kRowUnroll; u++) {
         // the four lanes of a quad hold one group; n_chunks % 4 == 0 keeps quads uniform
-        const uint32_t gmax = quad_max_u32(chunk_absmax(raw[u]));
-        const int ex = local_exponent<CEIL>(gmax, g);
-        eb[u] = (uint32_t)(ex + 127);
-        f[u] = group_factor(gmax, ex, g);
-        wide |= factor_is_wide(f[u]);
+        gmax[u] = quad_max_u32(chunk_absmax(raw[u]));
+        sub_min = gmax[u] - 1u < sub_min ? gmax[u] - 1u : sub_min;     // (a zero group wraps to the largest value)
+        fast_group(gmax[u], g, eb[u], f[u], min_fb);
     }
-    const bool any_wide = __any(wide);
+    // the integer form does not cover a subnormal tensor or group maximum, nor factors beyond the finite range
+    bool any_wide = false;
+    if (__any(!g.fast || sub_min < 127u || (int)min_fb <= g.wide_at)) {
+        bool wide = false;
+#pragma unroll
+        for (int u = 0; u < kRowUnroll; u++) {
+            const int ex = local_exponent<CEIL>(gmax[u], g);
+            eb[u] = (uint32_t)(ex + 127);
+            f[u] = group_factor(gmax[u], ex, g);
+            wide |= factor_is_wide(f[u]);
+        }
+        any_wide = __any(wide);
+    }
 #pragma unroll
     for (int u = 0; u < kRowUnroll; u++) {
         const int64_t id = base + (int64_t)u * kQuantThreads;
@@ -264,18 +348,48 @@ __global__ __launch_bounds__(kQuantThreads) void k_quant_row(const uint16_t *__r
 //    transposed output row; the pieces are collected in LDS and, after the only barrier,
 //    8 lanes write the 128 bytes of each transposed row.
 constexpr int kTile = 128;
-constexpr int kTilePitch = kTile + 8;   // bytes per staged output row (8-byte aligned pieces, some bank spread; the
-                                        // spare bytes carry the column exponents)
+constexpr int kTilePitch = kTile + 8;   // bytes per staged output row (8-byte aligned pieces, some bank spread)
+
+// LDS of a workgroup that converts tiles: the transposed codes of the tile, and the exponent bytes of the tile's
+// 128 x 4 row groups and 4 x 128 column groups, which leave as one 4-byte store per row / per column (single-byte
+// stores from every lane cost several times the cache-line visits and were ~3.5 us of a 64 MiB tensor's 42 us).
+struct TileLds {
+    __attribute__((aligned(16))) uint8_t tt[kTile][kTilePitch];   // transposed codes [column][row]
+    __attribute__((aligned(8))) uint8_t te[4][kTile];             // row-group exponents [column group of the tile][row]
+    __attribute__((aligned(8))) uint8_t tc[4][kTile];             // column-group exponents [row group of the tile][column]
+    uint32_t redo;                                                // bit k: the workgroup's tile k needs the general form
+};
+
+// The converter writes two bytes of its destination and keeps the other two, so its destination is also an
+// input.  For the first write into a word that input is dead weight: handing it a register that is free
+// anyway (one of the operands) saves the move that a zero would need.
+__device__ __forceinline__ uint32_t cvt_lo_fresh(float a, float b)
+{
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)__float_as_uint(a), false);
+}
+__device__ __forceinline__ uint32_t cvt_hi(float a, float b, uint32_t word)
+{
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)word, true);
+}
+
+// What a lane needs to know about its part of a tile: byte offsets from wave-uniform tile bases (32 bits are
+// enough inside a tile: the host checks 128 * row pitch < 2^31), and which of its rows / columns exist.
+struct LanePlace {
+    uint32_t q_row_off;    // from q_row + r0 * cols + c0 to this lane's first row, this lane's 8 columns
+    bool col_ok;           // this lane's 8 columns exist (cols % 32 == 0: all or none)
+    int n_ok;              // how many of this lane's 8 rows exist
+};
 
 // Codes of one lane's 8 x 8 values for both groupings.  Rows are taken two at a time: the
 // converter packs two values into two neighbouring bytes, so feeding it the same column
 // of two consecutive rows builds the transposed 8-row pieces without any byte shuffling.
-// rbytes / cbytes hold the 8 row-group and the 8 column-group exponent bytes.
-// n_ok = how many of this lane's 8 rows exist (row grouping alone allows any row count).
-template <bool ROW, bool COL, bool FUSED>
+// rbytes / cbytes hold the 8 row-group and the 8 column-group exponent bytes (needed by the two-product form).
+// FULL: every row and column of the tile exists, nothing is predicated.
+template <bool ROW, bool COL, bool FUSED, bool FULL>
 __device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&rf)[8], const uint32_t (&rbytes)[2],
                                            const float (&cf)[8], const uint32_t (&cbytes)[2], float inv_s, int n_ok,
-                                           uint8_t *__restrict__ q_row_lane, int64_t cols, uint32_t (&pieces)[8][2])
+                                           uint8_t *__restrict__ q_row_tile, uint32_t q_row_off, uint32_t cols,
+                                           uint32_t (&pieces)[8][2])
 {
 #pragma unroll
     for (int pr = 0; pr < 4; pr++) {
@@ -297,9 +411,9 @@ __device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&
                 const uint32_t eb = (rbytes[it >> 2] >> (8 * (it & 3))) & 0xFFu;
                 float y[8];
 #pragma unroll
-                for (int j = 0; j < 8; j++) y[j] = scaled<FUSED>(x[k][j], rf[it], eb, inv_s);
-                const uint2 out = make_uint2(cvt4_e4m3_sat(y[0], y[1], y[2], y[3]), cvt4_e4m3_sat(y[4], y[5], y[6], y[7]));
-                if (it < n_ok) st_stream8(q_row_lane + it * cols, out);
+                for (int j = 0; j < 8; j++) y[j] = clamp448(scaled<FUSED>(x[k][j], rf[it], eb, inv_s));
+                const uint2 out = make_uint2(cvt_hi(y[2], y[3], cvt_lo_fresh(y[0], y[1])), cvt_hi(y[6], y[7], cvt_lo_fresh(y[4], y[5])));
+                if (FULL || it < n_ok) st_stream8(q_row_tile + (q_row_off + (uint32_t)it * cols), out);
             }
         }
         if (!COL) continue;
@@ -310,50 +424,75 @@ __device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&
             const float b = clamp448(scaled<FUSED>(x[1][j], cf[j], eb, inv_s));
             uint32_t &word = pieces[j][pr >> 1];
             if (pr & 1)
-                word = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)word, true);
+                word = cvt_hi(a, b, word);
             else
-                word = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)word, false);
+                word = cvt_lo_fresh(a, b);
         }
     }
 }
 
-// The two-product form of tile_codes, out of line: it runs only for tiles that hold a group of
-// tiny nonzero values under a small global maximum, and inlining it next to the one-product
-// form doubled the code and the register pressure of every tile.  Its operands travel through
-// a struct in private memory that only the cold branch ever fills.
-struct WideTile {
-    uint4 raw[8];
-    float rf[8], cf[8];
-    uint32_t rbytes[2], cbytes[2];
-    float inv_s;
-    int n_ok;
-    uint8_t *q_row_lane;
-    int64_t cols;
-    uint32_t pieces[8][2];
-};
-
+// Group maxima of a lane's part of a tile: rmax[it] = maximum of the row group that holds this lane's 8 columns
+// of row it (a quad of lanes shares it), cmax[j] = maximum of the column group of this lane's column j over the
+// wave's 32 rows (this lane's 8 rows and those of the lanes 16, 32 and 48 further on).
 template <bool ROW, bool COL>
-__device__ __attribute__((noinline)) void tile_codes_wide(WideTile *w)
+__device__ __forceinline__ void tile_group_maxima(const uint4 (&raw)[8], uint32_t (&rmax)[8], uint32_t (&cmax)[8])
 {
-    tile_codes<ROW, COL, false>(w->raw, w->rf, w->rbytes, w->cf, w->cbytes, w->inv_s, w->n_ok, w->q_row_lane, w->cols,
-                                w->pieces);
+    uint32_t pm[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int it = 0; it < 8; it++) {
+        const uint32_t m0 = raw[it].x & kMagMask, m1 = raw[it].y & kMagMask, m2 = raw[it].z & kMagMask,
+                       m3 = raw[it].w & kMagMask;
+        if (COL) {
+            pm[0] = pk_max_u16(pm[0], m0);
+            pm[1] = pk_max_u16(pm[1], m1);
+            pm[2] = pk_max_u16(pm[2], m2);
+            pm[3] = pk_max_u16(pm[3], m3);
+        }
+        if (ROW) {
+            const uint32_t p = pk_max_u16(pk_max_u16(m0, m1), pk_max_u16(m2, m3));
+            const uint32_t lo = p & 0xFFFFu, hi = p >> 16;
+            rmax[it] = quad_max_u32(lo > hi ? lo : hi);
+        }
+    }
+    if (COL) {
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 16, 64));
+            pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 32, 64));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) cmax[j] = (pm[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+    }
 }
 
 struct TileShape {
     int64_t rows, cols, ld;
 };
 
+__device__ __forceinline__ bool tile_is_full(const TileShape &sh, int64_t r0, int64_t c0)
+{
+    return r0 + kTile <= sh.rows && c0 + kTile <= sh.cols;
+}
+
 // This lane's 8 x 16 bytes of the tile whose first element is (r0, c0); zeros outside X.
 __device__ __forceinline__ void load_tile(uint4 (&raw)[8], const uint16_t *__restrict__ x, const TileShape &sh, int64_t r0,
                                           int64_t c0)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane >> 4, ch = lane & 15;
-    const int64_t col = c0 + ch * 8, rbase = r0 + wave * kGroup + rl * 8;
-    const bool ok = col < sh.cols;
+    const uint16_t *tile = x + r0 * sh.ld + c0;                                      // wave-uniform
+    const uint32_t ld = (uint32_t)sh.ld;
+    const uint32_t off = (uint32_t)(wave * kGroup + rl * 8) * ld + (uint32_t)ch * 8;  // elements, < 2^31 (host check)
+    if (tile_is_full(sh, r0, c0)) {
 #pragma unroll
-    for (int it = 0; it < 8; it++) {
-        raw[it] = make_uint4(0, 0, 0, 0);
-        if (ok && rbase + it < sh.rows) raw[it] = ld_stream16(x + (rbase + it) * sh.ld + col);
+        for (int it = 0; it < 8; it++) raw[it] = ld_stream16(tile + (off + (uint32_t)it * ld));
+    } else {
+        const bool ok = c0 + ch * 8 < sh.cols;
+        const int64_t rbase = r0 + wave * kGroup + rl * 8;
+#pragma unroll
+        for (int it = 0; it < 8; it++) {
+            raw[it] = make_uint4(0, 0, 0, 0);
+            if (ok && rbase + it < sh.rows) raw[it] = ld_stream16(tile + (off + (uint32_t)it * ld));
+        }
     }
 }
 
@@ -369,127 +508,120 @@ __device__ __forceinline__ uint32_t tile_absmax(const uint4 (&raw)[8])
     return lo > hi ? lo : hi;
 }
 
-// Exponents and codes of one 128 x 128 tile from the registers that hold it.  With COL the body
-// contains one workgroup barrier, and the staging buffer tt stays in use until the next one.
-// STAGE_E: the column exponents leave through LDS as 4-byte stores (see below); the one-launch
-// kernel, which holds its tiles in registers and has none to spare, stores them byte by byte.
-template <bool ROW, bool COL, bool CEIL, bool STAGE_E>
-__device__ __forceinline__ void quant_tile_body(const uint4 (&raw)[8], const TileShape &sh, int64_t r0, int64_t c0,
+// Exponents and codes of one 128 x 128 tile from the registers that hold it, in one of two forms.
+//   FAST: for tiles that lie wholly inside X.  Nothing is predicated, the exponents come from the integer
+//         form (fast_group) and every code from one multiplication by 2^-e (1/s).  That form does not cover
+//         a subnormal tensor or group maximum, nor a factor beyond the finite range (tiny nonzero groups under
+//         a small global maximum): the return value says whether this wave met one, and the tile then has to
+//         be done again in the general form (what was stored is overwritten).
+//   general (!FAST): any tile, any finite data: predicated accesses, local_exponent, two-product codes.
+// The two forms never sit side by side in a loop body: a kernel runs the fast form over its tiles and the
+// general form afterwards for the (rare) tiles that need it, so that the fast form's registers stay few.
+// The body contains one workgroup barrier; the LDS staging area stays in use until the caller's next barrier.
+template <bool ROW, bool COL, bool CEIL, bool FAST>
+__device__ __forceinline__ bool quant_tile_body(const uint4 (&raw)[8], const TileShape &sh, int64_t r0, int64_t c0,
                                                 const GlobalScale &g, uint8_t *__restrict__ q_row,
                                                 uint8_t *__restrict__ e_row, uint8_t *__restrict__ q_col,
-                                                uint8_t *__restrict__ e_col, uint8_t (*tt)[kTilePitch])
+                                                uint8_t *__restrict__ e_col, TileLds &lds)
 {
+    constexpr bool FULL = FAST;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane >> 4, ch = lane & 15;
     const int64_t rows = sh.rows, cols = sh.cols;
-    const int64_t col = c0 + ch * 8;
-    const int64_t rbase = r0 + wave * kGroup + rl * 8;           // first of this lane's 8 rows
-    const bool ok = col < cols && rbase < rows;                  // cols % 32 == 0: whole column chunks
-    const int64_t left = rows - rbase;
-    const int n_ok = !ok ? 0 : (left < 8 ? (int)left : 8);       // (always 0 or 8 with COL: rows % 32 == 0)
+    const int row_in_tile = wave * kGroup + rl * 8;              // first of this lane's 8 rows
+    const bool ok = FULL || (c0 + ch * 8 < cols && r0 + row_in_tile < rows);     // cols % 32 == 0: whole column chunks
+    const int64_t left = rows - (r0 + row_in_tile);
+    const int n_ok = FULL ? 8 : (!ok ? 0 : (left < 8 ? (int)left : 8));         // (always 0 or 8 with COL: rows % 32 == 0)
     const int64_t n_rgroups = rows / kGroup, n_cgroups = cols / kGroup;
 
-    // group maxima: a row group (32 columns of one row) lives in a quad of lanes; a column
-    // group in this lane's 8 rows and those of the lanes 16, 32 and 48 further on
-    uint32_t pm[4] = {0, 0, 0, 0};
+    // group maxima, then exponent bytes and factors
     float rf[8], cf[8];
     uint32_t rbytes[2] = {0, 0}, cbytes[2] = {0, 0};
-    bool wide = false;
+    bool redo = false;
+    {
+        uint32_t rmax[8], cmax[8];
+        tile_group_maxima<ROW, COL>(raw, rmax, cmax);
+        if (FAST) {
+            uint32_t sub_min = ~0u, min_fb = 255u;
 #pragma unroll
-    for (int it = 0; it < 8; it++) {
-        const uint32_t m0 = raw[it].x & kMagMask, m1 = raw[it].y & kMagMask, m2 = raw[it].z & kMagMask,
-                       m3 = raw[it].w & kMagMask;
-        if (COL) {
-            pm[0] = pk_max_u16(pm[0], m0);
-            pm[1] = pk_max_u16(pm[1], m1);
-            pm[2] = pk_max_u16(pm[2], m2);
-            pm[3] = pk_max_u16(pm[3], m3);
-        }
-        if (ROW) {
-            const uint32_t p = pk_max_u16(pk_max_u16(m0, m1), pk_max_u16(m2, m3));
-            const uint32_t lo = p & 0xFFFFu, hi = p >> 16;
-            const uint32_t gmax = quad_max_u32(lo > hi ? lo : hi);
-            const int ex = local_exponent<CEIL>(gmax, g);
-            rf[it] = group_factor(gmax, ex, g);
-            wide |= factor_is_wide(rf[it]);
-            rbytes[it >> 2] |= (uint32_t)(ex + 127) << (8 * (it & 3));
-        }
-    }
-    if (COL) {
+            for (int i = 0; i < 8; i++) {
+                uint32_t byte;
+                if (ROW) {
+                    sub_min = rmax[i] - 1u < sub_min ? rmax[i] - 1u : sub_min;   // (a zero group wraps to the largest value)
+                    fast_group(rmax[i], g, byte, rf[i], min_fb);
+                    rbytes[i >> 2] |= byte << (8 * (i & 3));
+                }
+                if (COL) {
+                    sub_min = cmax[i] - 1u < sub_min ? cmax[i] - 1u : sub_min;
+                    fast_group(cmax[i], g, byte, cf[i], min_fb);
+                    cbytes[i >> 2] |= byte << (8 * (i & 3));
+                }
+            }
+            redo = __any(!g.fast || sub_min < 127u || (int)min_fb <= g.wide_at);
+        } else {
 #pragma unroll
-        for (int d = 0; d < 4; d++) {
-            pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 16, 64));
-            pm[d] = pk_max_u16(pm[d], (uint32_t)__shfl_xor((int)pm[d], 32, 64));
-        }
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            const uint32_t m = (pm[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-            const int ex = local_exponent<CEIL>(m, g);
-            cf[j] = group_factor(m, ex, g);
-            wide |= factor_is_wide(cf[j]);
-            cbytes[j >> 2] |= (uint32_t)(ex + 127) << (8 * (j & 3));
+            for (int i = 0; i < 8; i++) {
+                rf[i] = cf[i] = 0.0f;     // (not used by the two-product form)
+                if (ROW) rbytes[i >> 2] |= (uint32_t)(local_exponent<CEIL>(rmax[i], g) + 127) << (8 * (i & 3));
+                if (COL) cbytes[i >> 2] |= (uint32_t)(local_exponent<CEIL>(cmax[i], g) + 127) << (8 * (i & 3));
+            }
         }
     }
 
-    if (ROW && (lane & 3) == 0) {
-#pragma unroll
-        for (int it = 0; it < 8; it++)
-            if (it < n_ok) e_row[(rbase + it) * n_cgroups + (col >> 5)] = (uint8_t)(rbytes[it >> 2] >> (8 * (it & 3)));
-    }
-    // The exponent bytes of a column's four row groups in this tile are neighbours in e_col: they are
-    // collected in the 8 spare bytes of the staging rows and go out as one 4-byte store per column
-    // (single-byte stores from every wave cost four times the cache-line visits).
-    const bool whole_groups = STAGE_E && (rows & (kTile - 1)) == 0;    // all four row groups of every tile exist
-    if (COL && rl == 0) {
-        if (whole_groups) {
-#pragma unroll
-            for (int j = 0; j < 8; j++) tt[ch * 8 + j][kTile + wave] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
-        } else if (ok) {
-            const int64_t gidx = (r0 >> 5) + wave;
-#pragma unroll
-            for (int j = 0; j < 8; j++) e_col[(col + j) * n_rgroups + gidx] = (uint8_t)(cbytes[j >> 2] >> (8 * (j & 3)));
-        }
-    }
+    // exponent bytes into LDS: the first lane of a quad holds its row group's bytes of 8 consecutive rows, the
+    // first 16 lanes of a wave the bytes of their 8 columns for the wave's row group
+    if (ROW && (lane & 3) == 0) *reinterpret_cast<uint2 *>(&lds.te[ch >> 2][row_in_tile]) = make_uint2(rbytes[0], rbytes[1]);
+    if (COL && rl == 0) *reinterpret_cast<uint2 *>(&lds.tc[wave][ch * 8]) = make_uint2(cbytes[0], cbytes[1]);
 
     uint32_t pieces[8][2];
-#pragma unroll
-    for (int j = 0; j < 8; j++) pieces[j][0] = pieces[j][1] = 0;
-    uint8_t *q_row_lane = ROW ? q_row + rbase * cols + col : nullptr;
-    if (__any(wide)) {
-        WideTile w;
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-            w.raw[i] = raw[i];
-            w.rf[i] = ROW ? rf[i] : 0.0f;
-            w.cf[i] = COL ? cf[i] : 0.0f;
-            w.pieces[i][0] = w.pieces[i][1] = 0;
-        }
-        w.rbytes[0] = rbytes[0]; w.rbytes[1] = rbytes[1];
-        w.cbytes[0] = cbytes[0]; w.cbytes[1] = cbytes[1];
-        w.inv_s = g.inv_s; w.n_ok = n_ok; w.q_row_lane = q_row_lane; w.cols = cols;
-        tile_codes_wide<ROW, COL>(&w);
-#pragma unroll
-        for (int j = 0; j < 8; j++) { pieces[j][0] = w.pieces[j][0]; pieces[j][1] = w.pieces[j][1]; }
-    } else {
-        tile_codes<ROW, COL, true>(raw, rf, rbytes, cf, cbytes, g.inv_s, n_ok, q_row_lane, cols, pieces);
-    }
-    if (!COL) return;
+    uint8_t *q_row_tile = ROW ? q_row + r0 * cols + c0 : nullptr;                       // wave-uniform
+    const uint32_t q_row_off = (uint32_t)row_in_tile * (uint32_t)cols + (uint32_t)ch * 8;
+    tile_codes<ROW, COL, FAST, FULL>(raw, rf, rbytes, cf, cbytes, g.inv_s, n_ok, q_row_tile, q_row_off, (uint32_t)cols, pieces);
 
     // the 8 rows of this lane form one 8-byte piece of each of its 8 transposed rows
+    if (COL) {
 #pragma unroll
-    for (int j = 0; j < 8; j++)
-        *reinterpret_cast<uint2 *>(&tt[ch * 8 + j][wave * kGroup + rl * 8]) = make_uint2(pieces[j][0], pieces[j][1]);
+        for (int j = 0; j < 8; j++)
+            *reinterpret_cast<uint2 *>(&lds.tt[ch * 8 + j][row_in_tile]) = make_uint2(pieces[j][0], pieces[j][1]);
+    }
     __syncthreads();
+    if (COL) {
+        uint8_t *q_col_tile = q_col + c0 * rows + r0;                                    // wave-uniform
 #pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int idx = tid + k * kQuantThreads, c = idx >> 3, piece = idx & 7;
-        if (c0 + c < cols && r0 + piece * 16 < rows) {
-            const uint32_t *src = reinterpret_cast<const uint32_t *>(&tt[c][piece * 16]);
-            st_stream16(q_col + (c0 + c) * rows + r0 + piece * 16, make_uint4(src[0], src[1], src[2], src[3]));
+        for (int k = 0; k < 4; k++) {
+            const int idx = tid + k * kQuantThreads, c = idx >> 3, piece = idx & 7;
+            if (FULL || (c0 + c < cols && r0 + piece * 16 < rows)) {
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(&lds.tt[c][piece * 16]);
+                st_stream16(q_col_tile + ((uint32_t)c * (uint32_t)rows + (uint32_t)piece * 16), make_uint4(src[0], src[1], src[2], src[3]));
+            }
         }
     }
-    if (whole_groups && tid < kTile && c0 + tid < cols)
-        *reinterpret_cast<uint32_t *>(e_col + (c0 + tid) * n_rgroups + (r0 >> 5)) =
-            *reinterpret_cast<const uint32_t *>(&tt[tid][kTile]);
+    // Exponent bytes: threads 0..127 each own a row of the tile (its 4 row-group bytes are neighbours in e_row),
+    // threads 128..255 a column (its 4 column-group bytes are neighbours in e_col).
+    if (ROW && tid < kTile) {
+        const int r = tid;
+        const uint32_t word = (uint32_t)lds.te[0][r] | (uint32_t)lds.te[1][r] << 8 | (uint32_t)lds.te[2][r] << 16 | (uint32_t)lds.te[3][r] << 24;
+        uint8_t *dst = e_row + (r0 + r) * n_cgroups + (c0 >> 5);
+        if (FULL && (n_cgroups & 3) == 0) {
+            *reinterpret_cast<uint32_t *>(dst) = word;
+        } else if (r0 + r < rows) {
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                if (c0 + q * kGroup < cols) dst[q] = (uint8_t)(word >> (8 * q));
+        }
+    }
+    if (COL && tid >= kTile) {
+        const int c = tid - kTile;
+        const uint32_t word = (uint32_t)lds.tc[0][c] | (uint32_t)lds.tc[1][c] << 8 | (uint32_t)lds.tc[2][c] << 16 | (uint32_t)lds.tc[3][c] << 24;
+        uint8_t *dst = e_col + (c0 + c) * n_rgroups + (r0 >> 5);
+        if (FULL && (n_rgroups & 3) == 0) {
+            *reinterpret_cast<uint32_t *>(dst) = word;
+        } else if (c0 + c < cols) {
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                if (r0 + q * kGroup < rows) dst[q] = (uint8_t)(word >> (8 * q));
+        }
+    }
+    return redo;
 }
 
 template <bool ROW, bool CEIL>
@@ -500,16 +632,25 @@ __global__ __launch_bounds__(kQuantThreads, 4) void k_quant_tile(const uint16_t 
                                                                  uint8_t *__restrict__ e_col, float *__restrict__ s_global)
 {
     __shared__ uint32_t red[kQuantThreads / kWave];
-    __shared__ __attribute__((aligned(16))) uint8_t tt[kTile][kTilePitch]; // transposed codes [column][row]
+    __shared__ TileLds lds;
 
-    const GlobalScale g = fold_global_scale(partial, n_partial, red);
+    converter_saturates();
+    if (threadIdx.x == 0) lds.redo = 0;
+    const GlobalScale g = fold_global_scale<CEIL>(partial, n_partial, red);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *s_global = g.s;
 
     const TileShape sh = {rows, cols, ld};
     const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
     uint4 raw[8];
     load_tile(raw, x, sh, r0, c0);
-    quant_tile_body<ROW, true, CEIL, true>(raw, sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
+    bool general = true;
+    if (tile_is_full(sh, r0, c0)) {        // (lds.redo was cleared before the barrier inside fold_global_scale)
+        if (quant_tile_body<ROW, true, CEIL, true>(raw, sh, r0, c0, g, q_row, e_row, q_col, e_col, lds) && (threadIdx.x & 63) == 0)
+            atomicOr(&lds.redo, 1u);
+        __syncthreads();
+        general = lds.redo != 0;
+    }
+    if (general) quant_tile_body<ROW, true, CEIL, false>(raw, sh, r0, c0, g, q_row, e_row, q_col, e_col, lds);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -564,8 +705,10 @@ __global__ __launch_bounds__(kQuantThreads, 2) void k_quant_persist(const uint16
                                                                     float *__restrict__ s_global)
 {
     __shared__ uint32_t red[kQuantThreads / kWave + 1];
-    __shared__ __attribute__((aligned(16))) uint8_t tt[kTile][kTilePitch];
+    __shared__ TileLds lds;
 
+    converter_saturates();
+    if (threadIdx.x == 0) lds.redo = 0;      // (read only behind the barriers of the meeting point)
     const TileShape sh = {rows, cols, ld};
     const int G = (int)gridDim.x, first = (int)blockIdx.x;
     auto origin = [&](int t, int64_t &r0, int64_t &c0) {
@@ -647,19 +790,39 @@ __global__ __launch_bounds__(kQuantThreads, 2) void k_quant_persist(const uint16
         amax_bits = red[0];
         for (int i = 1; i < kQuantThreads / kWave; i++) amax_bits = red[i] > amax_bits ? red[i] : amax_bits;
     }
-    const GlobalScale g = make_global_scale(amax_bits);
+    const GlobalScale g = make_global_scale<CEIL>(amax_bits);
     if (first == 0 && threadIdx.x == 0) *s_global = g.s;
 
-    // walk 2: codes and exponents from the registers
+    // walk 2: codes and exponents from the registers, in the fast form
+    uint32_t edge = 0;       // tiles that reach beyond X: left to the general form
 #pragma unroll
     for (int k = 0; k < kKeep; k++) {
         const int t = kept_tile(k);
         if (t < n_tiles) {
             int64_t r0, c0;
             origin(t, r0, c0);
-            quant_tile_body<ROW, COL, CEIL, false>(keep[k], sh, r0, c0, g, q_row, e_row, q_col, e_col, tt);
-            if (COL) __syncthreads();
+            if (tile_is_full(sh, r0, c0)) {
+                if (quant_tile_body<ROW, COL, CEIL, true>(keep[k], sh, r0, c0, g, q_row, e_row, q_col, e_col, lds) &&
+                    (threadIdx.x & 63) == 0)
+                    atomicOr(&lds.redo, 1u << k);
+                __syncthreads();
+            } else {
+                edge |= 1u << k;
+            }
         }
+    }
+    // walk 3 (rare): the tiles the fast form does not cover, fetched again and done in the general form
+    __syncthreads();
+    const uint32_t again = lds.redo | edge;
+#pragma unroll 1
+    for (int k = 0; k < kKeep; k++) {
+        if (!((again >> k) & 1u)) continue;
+        int64_t r0, c0;
+        origin(kept_tile(k), r0, c0);
+        uint4 ra[8];
+        load_tile(ra, x, sh, r0, c0);
+        quant_tile_body<ROW, COL, CEIL, false>(ra, sh, r0, c0, g, q_row, e_row, q_col, e_col, lds);
+        __syncthreads();
     }
 }
 
@@ -762,9 +925,10 @@ static int quant_with_workspace(const void *x_bf16, int64_t rows, int64_t cols, 
     if (rows <= 0 || cols <= 0 || cols % kGroup || ld < cols) return MOSS_ERR_SHAPE;
     if (want_col && rows % kGroup) return MOSS_ERR_SHAPE;
     if (rows * (cols / 8) >= ((int64_t)1 << 40)) return MOSS_ERR_SHAPE;
+    if (ld >= ((int64_t)1 << 24) || (want_col && rows >= ((int64_t)1 << 24))) return MOSS_ERR_SHAPE;   // 32-bit offsets inside a tile
     if (ld % 8 || !moss_aligned16(x_bf16)) return MOSS_ERR_ALIGN;
-    if (want_row && !moss_aligned16(q_row)) return MOSS_ERR_ALIGN;
-    if (want_col && !moss_aligned16(q_col)) return MOSS_ERR_ALIGN;
+    if (want_row && (!moss_aligned16(q_row) || ((uintptr_t)e_row & 3))) return MOSS_ERR_ALIGN;
+    if (want_col && (!moss_aligned16(q_col) || ((uintptr_t)e_col & 3))) return MOSS_ERR_ALIGN;
     if (!moss_aligned16(workspace) || ((uintptr_t)s_global & 3)) return MOSS_ERR_ALIGN;
     if (!workspace || workspace_bytes < moss_quant_workspace_bytes(rows, cols, flags)) return MOSS_ERR_WORKSPACE;
 
@@ -876,9 +1040,10 @@ extern "C" int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows,
     if (rows <= 0 || cols <= 0 || cols % kGroup || ld < cols) return MOSS_ERR_SHAPE;
     if (want_col && rows % kGroup) return MOSS_ERR_SHAPE;
     if (rows * (cols / 8) >= ((int64_t)1 << 40)) return MOSS_ERR_SHAPE;
+    if (ld >= ((int64_t)1 << 24) || (want_col && rows >= ((int64_t)1 << 24))) return MOSS_ERR_SHAPE;   // 32-bit offsets inside a tile
     if (ld % 8 || !moss_aligned16(x_bf16)) return MOSS_ERR_ALIGN;
-    if (want_row && !moss_aligned16(q_row)) return MOSS_ERR_ALIGN;
-    if (want_col && !moss_aligned16(q_col)) return MOSS_ERR_ALIGN;
+    if (want_row && (!moss_aligned16(q_row) || ((uintptr_t)e_row & 3))) return MOSS_ERR_ALIGN;
+    if (want_col && (!moss_aligned16(q_col) || ((uintptr_t)e_col & 3))) return MOSS_ERR_ALIGN;
     if (((uintptr_t)s_global & 3) || ((uintptr_t)x_absmax_bits & 3)) return MOSS_ERR_ALIGN;
     // the producer's word takes the place of the partial maxima: one candidate, nothing to search
     return launch_codes((const uint16_t *)x_bf16, rows, cols, ld, want_row, want_col, ceil_mode, x_absmax_bits, 1, q_row,

@@ -84,6 +84,43 @@ def test_many_tiles_with_ragged_edges(oracle, shape, flag):
     check_against_oracle(oracle, xb, flag, f"many tiles {shape}")
 
 
+def with_adversarial_blocks(rows, cols, seed, scale=1.0):
+    """N(0, scale) with the adversarial 64 x 128 blocks of moss_inputs pasted into different tiles: whole tiles
+    that the fast form covers, tiles with zero groups, and tiles that need the general form (subnormal group
+    maxima, groups so tiny under the tensor maximum that 2^-e / s leaves the finite range)."""
+    rng = np.random.default_rng(seed)
+    x = mi.f32_to_bf16_bits((rng.standard_normal((rows, cols)) * scale).astype(np.float32))
+    blocks = mi.adversarial_activations(64, 128)
+    names = ["zeros", "zero_groups", "signed_zeros", "tiny", "tiny_zero_groups", "subnormal", "tiny_groups_under_large_max",
+             "sqrt2_boundary", "wide_range"]
+    places = [(r, c) for r in range(0, rows - 63, 192) for c in range(0, cols - 127, 384)]
+    for i, (r, c) in enumerate(places):
+        blk = blocks[names[i % len(names)]].copy()
+        if names[i % len(names)] in ("wide_range", "sqrt2_boundary", "tiny_groups_under_large_max"):
+            blk = mi.f32_to_bf16_bits(np.minimum(np.abs(mi.bf16_bits_to_f32(blk)), 2.0) * np.sign(mi.bf16_bits_to_f32(blk)))
+        x[r:r + 64, c:c + 128] = blk
+    return x
+
+
+@pytest.mark.parametrize("flag", [0, CEIL])
+def test_adversarial_blocks_inside_full_tiles_two_launch_path(oracle, flag):
+    check_against_oracle(oracle, with_adversarial_blocks(384, 768, 51), flag, "adversarial blocks, tile kernel")
+    check_against_oracle(oracle, with_adversarial_blocks(384, 800, 52, scale=300.0), flag, "adversarial blocks, large maximum")
+
+
+def test_tensor_with_a_subnormal_maximum_in_full_tiles(oracle):
+    rng = np.random.default_rng(53)
+    xb = mi.f32_to_bf16_bits((rng.standard_normal((256, 384)) * 2.0 ** -129).astype(np.float32))
+    for flag in (0, CEIL):
+        check_against_oracle(oracle, xb, flag, "subnormal maximum")
+
+
+@pytest.mark.parametrize("flag", [0, CEIL])
+def test_adversarial_blocks_on_the_one_launch_path(oracle, flag):
+    # 32 x 24 = 768 tiles: the one-launch kernel; a fifth of its tiles needs the general form
+    check_against_oracle(oracle, with_adversarial_blocks(4096, 3072, 54), flag, "adversarial blocks, one-launch kernel")
+
+
 def test_one_launch_path_when_the_meeting_times_out(oracle):
     # poll limit 0: every workgroup that finds the maximum not yet published computes it by itself
     xb = mi.heavy_tailed_activation(4128, 2080, seed=47)
