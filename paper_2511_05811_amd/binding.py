@@ -5,7 +5,8 @@ import os
 import re
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libmoss_hip.so")
+# MOSS_HIP_LIBRARY names another build of the same library (the tests load a sanitizer build this way)
+_LIB_PATH = os.environ.get("MOSS_HIP_LIBRARY") or os.path.join(_PKG, "libmoss_hip.so")
 _HEADER = os.path.join(os.path.dirname(_PKG), "include", "moss.h")
 _lib = None
 

@@ -909,14 +909,14 @@ static int launch_codes(const uint16_t *x, int64_t rows, int64_t cols, int64_t l
     return MOSS_OK;
 }
 
-// moss_quant_act_2level with its scratch (partial maxima, then the meeting words of the one-launch kernel) at
-// `workspace`, wherever that memory comes from.
-static int quant_with_workspace(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
-                                uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
-                                float *s_global, void *workspace, size_t workspace_bytes, void *stream)
+// What both quantizer entry points with a search for the maximum check before anything is launched
+// (the workspace apart).
+static int quant_check_args(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                            const uint8_t *q_row, const uint8_t *e_row, const uint8_t *q_col, const uint8_t *e_col,
+                            const float *s_global)
 {
     using namespace moss;
-    const bool want_row = flags & MOSS_Q_ROW, want_col = flags & MOSS_Q_COL, ceil_mode = flags & MOSS_EXP_CEIL;
+    const bool want_row = flags & MOSS_Q_ROW, want_col = flags & MOSS_Q_COL;
     if (flags & ~(MOSS_Q_ROW | MOSS_Q_COL | MOSS_EXP_CEIL)) return MOSS_ERR_UNSUPPORTED;
     if (!want_row && !want_col) return MOSS_ERR_UNSUPPORTED;
     if (!x_bf16 || !s_global) return MOSS_ERR_NULL;
@@ -929,8 +929,18 @@ static int quant_with_workspace(const void *x_bf16, int64_t rows, int64_t cols, 
     if (ld % 8 || !moss_aligned16(x_bf16)) return MOSS_ERR_ALIGN;
     if (want_row && (!moss_aligned16(q_row) || ((uintptr_t)e_row & 3))) return MOSS_ERR_ALIGN;
     if (want_col && (!moss_aligned16(q_col) || ((uintptr_t)e_col & 3))) return MOSS_ERR_ALIGN;
-    if (!moss_aligned16(workspace) || ((uintptr_t)s_global & 3)) return MOSS_ERR_ALIGN;
-    if (!workspace || workspace_bytes < moss_quant_workspace_bytes(rows, cols, flags)) return MOSS_ERR_WORKSPACE;
+    if ((uintptr_t)s_global & 3) return MOSS_ERR_ALIGN;
+    return MOSS_OK;
+}
+
+// moss_quant_act_2level with its scratch (partial maxima, then the meeting words of the one-launch kernel) at
+// `workspace`, wherever that memory comes from.  Arguments already checked.
+static int quant_with_workspace(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
+                                uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
+                                float *s_global, void *workspace, void *stream)
+{
+    using namespace moss;
+    const bool want_row = flags & MOSS_Q_ROW, want_col = flags & MOSS_Q_COL, ceil_mode = flags & MOSS_EXP_CEIL;
 
     hipStream_t st = (hipStream_t)stream;
     const uint16_t *x = (const uint16_t *)x_bf16;
@@ -973,8 +983,11 @@ extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t c
                                      uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
                                      float *s_global, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, workspace,
-                                workspace_bytes, stream);
+    const int rc = quant_check_args(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global);
+    if (rc != MOSS_OK) return rc;
+    if (!moss_aligned16(workspace)) return MOSS_ERR_ALIGN;
+    if (!workspace || workspace_bytes < moss_quant_workspace_bytes(rows, cols, flags)) return MOSS_ERR_WORKSPACE;
+    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, workspace, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1015,15 +1028,17 @@ extern "C" int moss_quant_act_2level_noalloc(const void *x_bf16, int64_t rows, i
                                              uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
                                              float *s_global, void *stream)
 {
+    int rc = quant_check_args(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global);
+    if (rc != MOSS_OK) return rc;
     // the scratch a shape needs must fit the array (today it does not grow with the shape, so this only
     // fails if the two ever drift apart)
     if (moss_quant_workspace_bytes(rows, cols, flags) > kScratchBytes) return MOSS_ERR_WORKSPACE;
     void *ws = nullptr;
-    const int rc = scratch_of_current_device(&ws);
+    rc = scratch_of_current_device(&ws);
     if (rc != MOSS_OK) return rc;
     // nothing in the array has to start at a known value: the partial maxima are written before they are
     // read, and the one-launch path clears its meeting words with a kernel of its own on the same stream
-    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, ws, kScratchBytes, stream);
+    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, ws, stream);
 }
 
 extern "C" int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,

@@ -60,6 +60,14 @@ def test_quant_argument_validation(L):
     assert q(FAKE, 32, 32, 32, 64) == 5                   # unknown flag
 
 
+def test_noalloc_argument_validation(L):
+    q = lambda x, rows, cols, ld, flags, qr=FAKE, er=FAKE, qc=FAKE, ec=FAKE, s=FAKE: \
+        L.moss_quant_act_2level_noalloc(x, rows, cols, ld, flags, qr, er, qc, ec, s, None)
+    assert q(FAKE, 32, 48, 48, 1) == 2
+    assert q(FAKE, 32, 32, 32, 0) == 5
+    assert q(FAKE, 32, 32, 32, 1, er=FAKE + 1) == 3       # exponent bytes leave as 4-byte words
+
+
 def test_producer_argument_validation(L):
     q = lambda x, rows, cols, ld, flags, mx=FAKE, qr=FAKE, er=FAKE, qc=FAKE, ec=FAKE, s=FAKE: \
         L.moss_quant_act_2level_given_max(x, rows, cols, ld, flags, mx, qr, er, qc, ec, s, None)

@@ -18,47 +18,50 @@ def bf16_bits(t):
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+SAMPLE = dict(n_rows=4, n_cols=4, n_rand=8192)     # per GEMM; config 3 carries the large sample on the same shapes
+
+
 def test_config5_block_linears_match_the_oracle(oracle):
+    """All five linears of the block, forward and backward: the BF16 tensors that reach the library (normalised
+    hidden states, attention output, SwiGLU product, and the gradients flowing back) quantize bit-exactly in both
+    groupings, and Y, dX and dW match the oracle's sums over those codes on sampled outputs."""
     b = blk.DecoderBlock(moss, torch, "moss", **blk.sizes_7b())
-    taps, grads = {}, {}
+    xin, yout, dy, dx = {}, {}, {}, {}
     inner = b.fn
 
     class Tap:
-        """records the BF16 input and output of every linear on the way through"""
+        """records, per linear, the BF16 input, the output, and the gradients of both"""
         @staticmethod
         def apply(x, layer):
-            y = inner.apply(x, layer)
             name = next(n for n, l in b.lin.items() if l is layer)
-            taps[name] = (x.detach(), y.detach())
-            y.register_hook(lambda g, name=name: grads.__setitem__(name, g.detach().clone()))
+            xi = x.view(x.shape)                    # a node of its own: its gradient is this linear's dX alone
+            if xi.requires_grad:
+                xi.register_hook(lambda g, name=name: dx.__setitem__(name, g.detach().clone()))
+            y = inner.apply(xi, layer)
+            xin[name], yout[name] = x.detach(), y.detach()
+            y.register_hook(lambda g, name=name: dy.__setitem__(name, g.detach().clone()))
             return y
     b.fn = Tap
     x = b.x.detach().requires_grad_(True)
     out = b.forward(x)
-    # forward operands of the two linears fed by non-linear layers: attention output -> o, SwiGLU -> down
-    rng = np.random.default_rng(55)
-    for name in ("o", "down"):
-        layer = b.lin[name]
-        xin, y = taps[name]
-        print(f"[config5] forward {name}: X {tuple(xin.shape)}", flush=True)
-        q, e, s = oracle.quant_act_2level(bf16_bits(xin), 0, 0)
-        assert scalar(layer.qx["s"]) == s
-        assert np.array_equal(u8(layer.qx["e_row"]), e) and np.array_equal(u8(layer.qx["q_row"]), q)
-        check_sampled(oracle, f"config5 {name} Y", y, (q, e, s), (u8(layer.wq), None, scalar(layer.s_w)), rng)
-    # backward: the gradient that reaches the down projection is the upstream gradient itself; the one
-    # that reaches gate has passed through the SwiGLU backward
     out.backward(b.upstream)
     torch.cuda.synchronize()
-    for name in ("down", "gate"):
-        layer = b.lin[name]
-        print(f"[config5] backward {name}: dW {tuple(layer.dw.shape)}", flush=True)
-        # dW = dY^T X from the column-grouped codes the library kept for this layer
-        qdy = (u8(layer.qdy["q_col"]), u8(layer.qdy["e_col"]), scalar(layer.qdy["s"]))
-        qx = (u8(layer.qx["q_col"]), u8(layer.qx["e_col"]), scalar(layer.qx["s"]))
-        gq, ge, gs = oracle.quant_act_2level(bf16_bits(grads[name]), 1, 0)
-        assert gs == qdy[2] and np.array_equal(qdy[0], gq) and np.array_equal(qdy[1], ge)
-        xin = taps[name][0]
-        qc, ec, sc = oracle.quant_act_2level(bf16_bits(xin), 1, 0)
-        assert sc == qx[2] and np.array_equal(qx[0], qc) and np.array_equal(qx[1], ec)
-        check_sampled(oracle, f"config5 {name} dW", layer.dw, qdy, qx, rng)
+    rng = np.random.default_rng(55)
+    for name, layer in b.lin.items():
+        print(f"[config5] {name}: X {tuple(xin[name].shape)} dY {tuple(dy[name].shape)}", flush=True)
+        st, owq, owq_t = oracle.weight_init(layer.w.cpu().numpy(), want_transpose=True)     # (no optimizer step has run)
+        assert scalar(layer.s_w) == st.s_cur and np.array_equal(u8(layer.wq), owq) and np.array_equal(u8(layer.wq_t), owq_t)
+        w, wt = (owq, None, st.s_cur), (owq_t, None, st.s_cur)
+        got = {}
+        for key, t, buf in (("x", xin[name], layer.qx), ("dy", dy[name], layer.qdy)):
+            bits = bf16_bits(t)
+            qr, er, s = oracle.quant_act_2level(bits, 0, 0)
+            qc, ec, _ = oracle.quant_act_2level(bits, 1, 0)
+            assert scalar(buf["s"]) == s, (name, key)
+            for k2, want in (("q_row", qr), ("e_row", er), ("q_col", qc), ("e_col", ec)):
+                assert np.array_equal(u8(buf[k2]), want), (name, key, k2)
+            got[key] = ((qr, er, s), (qc, ec, s))
+        check_sampled(oracle, f"config5 {name} Y", yout[name], got["x"][0], w, rng, **SAMPLE)
+        check_sampled(oracle, f"config5 {name} dX", dx[name], got["dy"][0], wt, rng, **SAMPLE)
+        check_sampled(oracle, f"config5 {name} dW", layer.dw, got["dy"][1], got["x"][1], rng, **SAMPLE)
     assert torch.isfinite(x.grad.float()).all()

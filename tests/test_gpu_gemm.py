@@ -151,7 +151,7 @@ def test_config1_linear_forward_chain(oracle):
         assert snr > (24.0 if mode else 15.0)
 
 
-def sampled_pairs(rng, M, N, n_rows=3, n_cols=3, n_rand=4096):
+def sampled_pairs(rng, M, N, n_rows=32, n_cols=32, n_rand=65536):
     ms, ns = [], []
     for r in rng.choice(M, n_rows, replace=False):
         ms.append(np.full(N, r)); ns.append(np.arange(N))
@@ -163,10 +163,12 @@ def sampled_pairs(rng, M, N, n_rows=3, n_cols=3, n_rand=4096):
     return np.concatenate(ms).astype(np.int64), np.concatenate(ns).astype(np.int64)
 
 
-def check_sampled(oracle, tag, out, oa, ob, rng):
+def check_sampled(oracle, tag, out, oa, ob, rng, **sample):
+    """Outputs on 32 random full rows, 32 random full columns, 65 536 random entries and the four corners (or the
+    smaller sample given) against the oracle's FP64 sums over the same codes."""
     (aq, ae, a_s), (bq, be, b_s) = oa, ob
     M, N = aq.shape[0], bq.shape[0]
-    ms, ns = sampled_pairs(rng, M, N)
+    ms, ns = sampled_pairs(rng, M, N, **sample)
     ref = oracle.gemm_sampled(aq, ae, a_s, bq, be, b_s, ms, ns)
     na = oracle.row_norms(aq, ae, a_s)[ms]
     nb = oracle.row_norms(bq, be, b_s)[ns]
@@ -175,10 +177,11 @@ def check_sampled(oracle, tag, out, oa, ob, rng):
     assert_close(got, ref, na, nb, out.dtype == torch.bfloat16, tag)
 
 
-@pytest.mark.parametrize("index", [0, 1, 2, 4])
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
 def test_config3_llama7b_linears_fwd_bwd_sampled(oracle, index):
-    """Y = X W^T, dX = dY W, dW = dY^T X at tokens = 8192 on the 7B shapes; codes and
-    exponents bit-exact, GEMM outputs checked on sampled rows / columns / entries."""
+    """Y = X W^T, dX = dY W, dW = dY^T X at tokens = 8192 on the five 7B shapes, in the launch configuration the
+    benchmark times; codes and exponents bit-exact, every GEMM output checked on 32 rows, 32 columns and
+    65 536 entries."""
     name, K, N = mi.LLAMA7B_LINEARS[index]
     print(f"[config3] linear {name}: tokens=8192 K={K} N={N}", flush=True)
     xb, wb, dyb = mi.config3_linear(index)
@@ -209,6 +212,25 @@ def test_config3_llama7b_linears_fwd_bwd_sampled(oracle, index):
     check_sampled(oracle, f"{name} Y", y, oxr, ow, rng)
     check_sampled(oracle, f"{name} dX", dx, odr, owt, rng)
     check_sampled(oracle, f"{name} dW", dw, odc, oxc, rng)
+
+
+# The (M, N, K) of the paper's table "Runtime of quantized FP8 GEMM" (Sec. 4.5.1).
+PAPER_GEMM_SHAPES = [(2048, 7168, 4096), (2048, 7168, 11008), (4096, 2048, 7168), (4096, 4096, 8192),
+                     (4096, 4096, 12288), (5120, 5120, 10240), (8192, 8192, 8192)]
+
+
+@pytest.mark.parametrize("shape", PAPER_GEMM_SHAPES)
+def test_paper_gemm_table_shapes_sampled(oracle, shape):
+    """The second GEMM workload: activations with level-2 exponents against per-tensor weights (a_e given, b_e
+    absent, as in the paper's kernel), random finite codes, BF16 output; 8 rows, 8 columns and 16 384 entries."""
+    M, N, K = shape
+    print(f"[gemm table] M={M} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(M + N + K)
+    a, b = finite_codes(rng, (M, K)), finite_codes(rng, (N, K))
+    ae = rng.integers(112, 128, size=(M, K // 32), dtype=np.uint8)
+    a_s, b_s = np.float32(0.02), np.float32(3.0e-4)
+    out = gpu_gemm(a, ae, a_s, b, None, b_s, out_dtype=torch.bfloat16)
+    check_sampled(oracle, f"table {shape}", out, (a, ae, a_s), (b, None, b_s), rng, n_rows=8, n_cols=8, n_rand=16384)
 
 
 def test_bf16_baseline_gemm_matches_fp64_product():
