@@ -435,7 +435,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mx_big(int64_t M, int64_t N, in
                     const uint4 v = *reinterpret_cast<const uint4 *>((ii ? pieceB : pieceA) + rr * 256 + ((cc ^ (rr & 15)) << 4));
                     const int64_t m = mw + (2 * rnd + ii) * 32 + rr, n = nw + cc * 8;
                     // (N % 8 == 0 and ld_out % 8 == 0 on this path: a piece is inside or outside as a whole)
-                    if (m < M && n < N) *reinterpret_cast<uint4 *>(o + m * ld_out + n) = v;
+                    // (streaming store: a BF16 output is an activation or gradient for a later layer, and leaving
+                    // it out of the last-level cache keeps the operands of the GEMMs in flight there)
+                    if (m < M && n < N) st_stream16(o + m * ld_out + n, v);
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staged rows consumed before they are overwritten
             }
