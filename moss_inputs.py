@@ -43,14 +43,15 @@ def config1(seed=1):
     return f32_to_bf16_bits(x), f32_to_bf16_bits(w)
 
 
-def heavy_tailed_activation(rows, cols, seed=2, outlier_frac=0.01, outlier_gain=100.0):
-    """0.5 * Student-t(nu=3) with a fraction of the channels multiplied by a gain (BF16 bits)."""
+def heavy_tailed_activation(rows, cols, seed=2, outlier_frac=0.01, outlier_gain=100.0, return_channels=False):
+    """0.5 * Student-t(nu=3) with a fraction of the channels multiplied by a gain (BF16 bits);
+    with return_channels also the indices of those channels."""
     rng = _rng(seed)
     x = (0.5 * rng.standard_t(3.0, size=(rows, cols))).astype(np.float32)
     n_out = max(1, int(round(outlier_frac * cols)))
     ch = rng.choice(cols, n_out, replace=False)
     x[:, ch] *= np.float32(outlier_gain)
-    return f32_to_bf16_bits(x)
+    return (f32_to_bf16_bits(x), np.sort(ch)) if return_channels else f32_to_bf16_bits(x)
 
 
 def config2(seed=2, rows=8192, cols=4096):

@@ -16,7 +16,10 @@
  *
  * Every function here is pinned by tests/test_oracle_*.py ("-m 'not gpu'"):
  * exhaustive E4M3 tables against a library cast, exact rational brute force,
- * closed forms and invariants.  Parity-unpinned functions: none.
+ * closed forms and invariants.  Parity-unpinned functions: none.  (The paper's
+ * SNR *gaps* between schemes come from activations of a trained model and are
+ * compared only softly on synthetic tensors; the functions that compute them
+ * are pinned.)
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
  */
@@ -467,6 +470,39 @@ int moss_oracle_swiglu_backward(const uint16_t *gate, const uint16_t *up, const 
         double sig = 1.0 / (1.0 + exp(-g));
         d_up[i] = d * (g * sig);
         d_gate[i] = d * u * (sig * (1.0 + g * (1.0 - sig)));
+    }
+    return MOSS_O_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* The two schemes the paper compares two-level microscaling with (Sec. 3.1, Proof 1: per-tensor
+ * quantization, Eq. 5, and per-group quantization, Eq. 6; the activation-SNR table of Sec. 4.5.2 uses
+ * groups of 128): one FP32 scale per `group` consecutive elements of a row, s_g = max|X_g| / 448
+ * (1 for an all-zero group), codes round(x / s_g) in E4M3, dequantized value code * s_g.
+ * group == 0 means one scale for the whole tensor.  x / s_g is evaluated in double (exact to well
+ * below an E4M3 rounding step) and rounded once.  dq receives the dequantized values, scales (may
+ * be NULL) the rows * cols / group scales (one for group == 0).                                  */
+int moss_oracle_groupwise_fp8(const uint16_t *x, int64_t rows, int64_t cols, int64_t group,
+                              uint8_t *q, float *scales, double *dq)
+{
+    if (!x || !q || !dq || rows <= 0 || cols <= 0 || group < 0) return MOSS_O_BAD_ARG;
+    if (group > 0 && cols % group) return MOSS_O_BAD_ARG;
+    const int64_t n = rows * cols, g = group > 0 ? group : n;
+    for (int64_t i = 0; i < n; i++)
+        if (!isfinite(bf16_to_double(x[i]))) return MOSS_O_NONFINITE;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < n / g; b++) {
+        double amax = 0.0;
+        for (int64_t i = b * g; i < (b + 1) * g; i++) {
+            double v = fabs(bf16_to_double(x[i]));
+            if (v > amax) amax = v;
+        }
+        float s = amax > 0.0 ? (float)amax / 448.0f : 1.0f;
+        if (scales) scales[b] = s;
+        for (int64_t i = b * g; i < (b + 1) * g; i++) {
+            q[i] = moss_oracle_e4m3_encode(bf16_to_double(x[i]) / (double)s);
+            dq[i] = moss_oracle_e4m3_decode(q[i]) * (double)s;
+        }
     }
     return MOSS_O_OK;
 }

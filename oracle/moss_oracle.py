@@ -79,6 +79,7 @@ def lib():
                                                C.c_void_p, C.c_void_p, C.c_float,
                                                C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.moss_oracle_row_norms.argtypes = [C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
+        L.moss_oracle_groupwise_fp8.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.moss_oracle_num_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -219,6 +220,18 @@ def row_norms(q, e, s):
     out = np.empty(R, np.float64)
     _check(lib().moss_oracle_row_norms(R, K, _p(q), _p(e), float(s), _p(out)), "row_norms")
     return out
+
+
+def groupwise_fp8(x_bf16_bits, group):
+    """The comparison schemes of Sec. 3.1 / 4.5.2: one FP32 scale per `group` consecutive elements of a row
+    (0: per tensor).  Returns (codes, scales, dequantized values in double)."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    rows, cols = x.shape
+    q = np.empty((rows, cols), np.uint8)
+    scales = np.empty(1 if group == 0 else rows * cols // group, np.float32)
+    dq = np.empty((rows, cols), np.float64)
+    _check(lib().moss_oracle_groupwise_fp8(_p(x), rows, cols, group, _p(q), _p(scales), _p(dq)), "groupwise_fp8")
+    return q, scales, dq
 
 
 def snr_db(x, dq):

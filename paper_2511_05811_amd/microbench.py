@@ -3,8 +3,7 @@
 
     python -m paper_2511_05811_amd.microbench scaling   # Table "Time usage to calculate per-tensor scaling factors" (Sec. 3.2)
                                                          # and the interval sweep of the scaling ablation (App.)
-    python -m paper_2511_05811_amd.microbench gemm      # Table "Runtime of quantized FP8 GEMM" (Sec. 4.3): its seven shapes
-    python -m paper_2511_05811_amd.microbench snr       # Sec. 3.1 Eq. 4 / SNR table: per-tensor vs two-level microscaling
+    python -m paper_2511_05811_amd.microbench gemm      # Table "Runtime of quantized FP8 GEMM" (Sec. 4.5.1): its seven shapes
     python -m paper_2511_05811_amd.microbench block     # Sec. 4 setting, one decoder block: tokens/s with the linears on the
                                                          # FP8 path vs BF16 GEMMs (attention, norms, SwiGLU: BF16 torch ops)
     python -m paper_2511_05811_amd.microbench producer  # SwiGLU that also hands the tensor maximum to the quantizer (Sec. 3.1,
@@ -14,8 +13,9 @@
 
 Each mode prints one JSON line.  Inputs are seeded and synthetic; the paper's own figures are
 quoted with the hardware they were measured on, as context only.  Everything that is timed
-runs in the HIP library; torch supplies memory, streams, events and the FP64 arithmetic of
-the SNR evaluation.
+runs in the HIP library; torch supplies memory, streams and events.  (The fidelity figures of
+Sec. 3.1 / 4.5.2, SNR of the library's codes against per-tensor and per-group-128 quantization,
+are computed by tests/test_gpu_fidelity.py through the CPU oracle, which this package never loads.)
 """
 import argparse
 import json
@@ -123,7 +123,7 @@ def scaling(moss, torch, small=False):
             "note": "paper figures: NVIDIA H800, context only"}
 
 
-# Sec. 4.3, table of quantized FP8 GEMM runtime: (M, N, K) and the paper's MOSS time on H800 (ms)
+# Sec. 4.5.1, table of quantized FP8 GEMM runtime: (M, N, K) and the paper's MOSS time on H800 (ms)
 GEMM_SHAPES = [((2048, 7168, 4096), 0.25), ((2048, 7168, 11008), 0.67), ((4096, 2048, 7168), 0.45), ((4096, 4096, 8192), 0.60),
                ((4096, 4096, 12288), 0.72), ((5120, 5120, 10240), 1.04), ((8192, 8192, 8192), 1.98)]
 
@@ -148,76 +148,6 @@ def gemm(moss, torch, small=False):
         out_rows.append({"M": M, "N": N, "K": K, "fp8_mx_ms": round(ms, 4), "fp8_mx_tflops": round(2.0 * M * N * K / ms / 1e9, 1),
                          "bf16_hand_gemm_ms": round(bf_ms, 4), "quant_x_ms": round(q_ms, 4), "paper_h800_moss_ms": paper_ms})
     return {"table": "gemm_shapes", "rows": out_rows, "note": "GEMM alone, operands already quantized; paper figures: NVIDIA H800, context only"}
-
-
-def _e4m3_table(torch, dev):
-    """Value of every E4M3 code (OCP E4M3: bias 7, no infinities, 0x7F / 0xFF are NaN), FP64."""
-    codes = torch.arange(256, device=dev)
-    sign = torch.where(codes >= 128, -1.0, 1.0).double()
-    ex = ((codes >> 3) & 15).double()
-    man = (codes & 7).double()
-    val = torch.where(ex == 0, man / 8.0 * 2.0 ** -6, (1.0 + man / 8.0) * torch.pow(torch.tensor(2.0, device=dev, dtype=torch.float64), ex - 7.0))
-    return sign * val
-
-
-def snr(moss, torch, small=False):
-    """SNR = 10 log10(sum x^2 / sum (x - DQ(Q(x)))^2) (Sec. 3.1, Eq. 4) of the library's codes on
-    heavy-tailed activations with outlier channels; the per-tensor row uses the library's
-    per-tensor cast (the weight path's initialisation) on the same tensor."""
-    dev = torch.device("cuda:0")
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(43)
-    rows, cols = (256, 512) if small else (8192, 4096)
-    # Student-t(3) x 0.5 = normal / sqrt(chi2_3 / 3); 1 % of the channels x 100
-    z = torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32)
-    chi = sum(torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32) ** 2 for _ in range(3))
-    x = 0.5 * z / torch.sqrt(chi / 3.0)
-    idx = torch.randperm(cols, generator=gen, device=dev)[: max(1, cols // 100)]
-    x[:, idx] *= 100.0
-    xb = x.to(torch.bfloat16)
-    xd = xb.double()
-    table = _e4m3_table(torch, dev)
-    power = float((xd * xd).sum())
-
-    def snr_db(deq):
-        return float(10.0 * torch.log10(torch.tensor(power) / float(((xd - deq) ** 2).sum())))
-
-    out = {}
-    for name, flag in (("moss_nearest", 0), ("moss_ceil", moss.MOSS_EXP_CEIL)):
-        q = moss.quant_act_2level(xb, moss.MOSS_Q_ROW | flag)
-        ss = torch.pow(torch.tensor(2.0, device=dev, dtype=torch.float64), q["e_row"].double() - 127.0)
-        deq = table[q["q_row"].long()] * float(q["s"][0]) * ss.repeat_interleave(32, dim=1)
-        out[name] = round(snr_db(deq), 2)
-        nonout = torch.ones(cols, dtype=torch.bool, device=dev); nonout[idx] = False
-        e = ((xd - deq) ** 2)[:, nonout].sum()
-        out[name + "_non_outlier_channels"] = round(float(10.0 * torch.log10((xd * xd)[:, nonout].sum() / e)), 2)
-    state = moss.new_wscale_state(dev)
-    wq, _ = moss.weight_autoscale_init(xb, state)
-    s = float(state[4:8].view(torch.float32)[0])
-    deq = table[wq.long()] * s
-    out["per_tensor"] = round(snr_db(deq), 2)
-    nonout = torch.ones(cols, dtype=torch.bool, device=dev); nonout[idx] = False
-    out["per_tensor_non_outlier_channels"] = round(float(10.0 * torch.log10((xd * xd)[:, nonout].sum() / ((xd - deq) ** 2)[:, nonout].sum())), 2)
-    # comparator, computed here with torch operations (not a library path): one FP32 scale per group of 128
-    # along the row, codes by rounding to the nearest E4M3 value
-    g128 = 128
-    xg = xd.view(rows, cols // g128, g128)
-    sg = (xg.abs().amax(dim=2, keepdim=True).float() / 448.0).double()
-    sg = torch.where(sg == 0, torch.ones_like(sg), sg)
-    y = (xg / sg).clamp(-448.0, 448.0)
-    vals = table[:127]                                           # 0 ... 448, ascending
-    near = vals[torch.bucketize(y.abs(), (vals[1:] + vals[:-1]) / 2.0)]
-    deq = (torch.sign(y) * near * sg).view(rows, cols)
-    out["per_group_128_fp32_scales"] = round(snr_db(deq), 2)
-    out["per_group_128_fp32_scales_non_outlier_channels"] = round(
-        float(10.0 * torch.log10((xd * xd)[:, nonout].sum() / ((xd - deq) ** 2)[:, nonout].sum())), 2)
-    return {"table": "snr", "unit": "dB", "shape": [rows, cols], "snr": out,
-            "note": "paper (activations of a trained 7B model): two-level 3.0-3.4 dB above per-group-128, 9.2-9.4 dB above per-tensor; "
-                    "synthetic heavy-tailed tensors stand in, so only the ordering is comparable.  moss_nearest rounds the local exponent "
-                    "to the closest power of two as Eq. 3 prints it, which lets a group maximum exceed 448 by up to sqrt(2) and "
-                    "saturate; moss_ceil rounds it up and never clips.  per_group_128_fp32_scales is a comparator computed with torch "
-                    "operations; its whole-tensor figure is flattered by the outlier channels, which carry most of the power and, being "
-                    "their groups' maxima, are represented exactly: compare the non-outlier columns"}
 
 
 def block(moss, torch, small=False):
@@ -376,7 +306,7 @@ def limits(moss, torch, small=False):
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["scaling", "gemm", "snr", "limits", "block", "producer"])
+    ap.add_argument("table", choices=["scaling", "gemm", "limits", "block", "producer"])
     ap.add_argument("--small", action="store_true", help="tiny shapes (used by the tests)")
     a = ap.parse_args(argv)
     import torch
@@ -384,7 +314,7 @@ def main(argv=None):
     if not torch.cuda.is_available():
         print("microbench needs the MI355X", file=sys.stderr)
         return 2
-    res = {"scaling": scaling, "gemm": gemm, "snr": snr, "limits": limits, "block": block, "producer": producer}[a.table](moss, torch, a.small)
+    res = {"scaling": scaling, "gemm": gemm, "limits": limits, "block": block, "producer": producer}[a.table](moss, torch, a.small)
     print(json.dumps(res))
     return 0
 

@@ -1,7 +1,6 @@
 """The side tables of paper_2511_05811_amd.microbench run end to end on small shapes and
 their outputs have the properties the paper states (Sec. 3.2: automatic scaling never
-lets a cast overflow and costs no max-reduction pass; Sec. 3.1: two-level microscaling
-is at least as faithful as a per-tensor scale)."""
+lets a cast overflow and costs no max-reduction pass)."""
 import pytest
 import torch
 
@@ -23,17 +22,6 @@ def test_scaling_table_small():
 def test_gemm_table_small():
     res = microbench.gemm(moss, torch, small=True)
     assert res["rows"][0]["fp8_mx_ms"] > 0 and res["rows"][0]["bf16_hand_gemm_ms"] > 0
-
-
-def test_snr_table_small():
-    res = microbench.snr(moss, torch, small=True)["snr"]
-    # with the exponent rounded up no value clips, and a local power-of-two scale can only help
-    assert res["moss_ceil"] >= res["per_tensor"] - 1e-6
-    # outlier channels dominate a per-tensor scale: the other channels gain most from local scales
-    assert res["moss_ceil_non_outlier_channels"] >= res["per_tensor_non_outlier_channels"] - 1e-6
-    # rounding the exponent to the nearest power of two (Eq. 3 as printed) clips group maxima by up
-    # to sqrt(2): its SNR is reported, not asserted
-    assert res["moss_nearest"] > 10.0
 
 
 def test_producer_table_small():

@@ -299,3 +299,44 @@ def test_snr_db_closed_forms(oracle):
     # scaling both by a constant changes nothing; doubling the noise amplitude costs 20 log10 2 dB
     assert abs(oracle.snr_db(3.0 * x, 3.0 * dq) - ref) < 1e-9
     assert abs(oracle.snr_db(x, x + 2.0 * (dq - x)) - (ref - 20.0 * math.log10(2.0))) < 1e-9
+
+
+def test_groupwise_comparators_against_exact_rationals(oracle):
+    """Per-tensor and per-group FP8 (Sec. 3.1, Eq. 5-6 context): scales, codes and dequantized values against a
+    brute force over the E4M3 grid in exact rational arithmetic, plus what the definitions imply."""
+    from fractions import Fraction
+    grid = [(c, Fraction(oracle.e4m3_decode(c))) for c in range(0x7F)]          # non-negative finite codes, ascending values
+
+    def nearest_code(y):                    # y: Fraction; ties to the even code, beyond 448 saturates
+        a = abs(y)
+        best = min(grid, key=lambda cv: (abs(cv[1] - a), cv[0] & 1))
+        return best[0] | (0x80 if y < 0 else 0)
+    rng = np.random.default_rng(61)
+    x = (rng.standard_t(3.0, size=(6, 64)) * 0.7).astype(np.float32)
+    x[2, 5] = 90.0; x[4, :32] = 0.0; x[0, 0] = -0.0
+    xb = mi.f32_to_bf16_bits(x)
+    xf = mi.bf16_bits_to_f32(xb)
+    for group in (0, 64, 32, 16):
+        q, scales, dq = oracle.groupwise_fp8(xb, group)
+        g = group or xf.size
+        blocks = xf.reshape(-1, g)
+        assert scales.shape == (blocks.shape[0],)
+        for b in range(blocks.shape[0]):
+            amax = np.abs(blocks[b]).max()
+            s = np.float32(amax) / np.float32(448.0) if amax > 0 else np.float32(1.0)
+            assert scales[b] == s
+            for j, v in enumerate(blocks[b]):
+                code = int(q.reshape(-1, g)[b, j])
+                if v == 0:
+                    assert code in (0x00, 0x80)
+                else:
+                    assert code == nearest_code(Fraction(float(v)) / Fraction(float(s))), (group, b, j)
+                assert dq.reshape(-1, g)[b, j] == oracle.e4m3_decode(code) * float(s)
+            if amax > 0:                    # the largest element of a group sits on the top code
+                assert (q.reshape(-1, g)[b] & 0x7F).max() == 0x7E
+    # every scheme keeps the three mantissa bits of E4M3 on its larger values: around 30 dB on this tensor
+    snrs = [oracle.snr_db(xf.astype(np.float64), oracle.groupwise_fp8(xb, g)[2]) for g in (0, 64, 32, 16)]
+    assert min(snrs) > 20.0 and max(snrs) < 40.0
+    # a group size that does not divide the row is refused
+    with pytest.raises(ValueError):
+        oracle.groupwise_fp8(xb, 48)
