@@ -475,6 +475,61 @@ int moss_oracle_swiglu_backward(const uint16_t *gate, const uint16_t *up, const 
 }
 
 /* ------------------------------------------------------------------ */
+/* The producer in front of the QKV and gate / up projections' quantizers (non-linear layers stay in
+ * BF16, Sec. 4.1): RMSNorm of a LLaMA block over each row of h [rows x cols],
+ *      y[r, c] = h[r, c] / sqrt(mean_c(h[r, :]^2) + eps) * gamma[c],
+ * from BF16 h and gamma, in double.  Backward for an upstream gradient dy, with the gradient that
+ * reaches h directly over the residual connection added in (d_res, may be NULL):
+ *      g = dy * gamma,  n = h / sqrt(mean(h^2) + eps),
+ *      d_h = d_res + (g - n * mean_c(g * n)) / sqrt(mean(h^2) + eps).
+ * (The gradient of gamma is not part of the path: it never meets a quantizer.)  Outputs are exact
+ * doubles; rounding to BF16 is left to the caller.                                                 */
+int moss_oracle_rmsnorm(const uint16_t *h, const uint16_t *gamma, double eps, int64_t rows, int64_t cols, double *y)
+{
+    if (!h || !gamma || !y || rows <= 0 || cols <= 0 || !(eps >= 0.0)) return MOSS_O_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; r++) {
+        double ss = 0.0;
+        for (int64_t c = 0; c < cols; c++) {
+            double v = bf16_to_double(h[r * cols + c]);
+            ss += v * v;
+        }
+        const double rms = sqrt(ss / (double)cols + eps);
+        for (int64_t c = 0; c < cols; c++)
+            y[r * cols + c] = bf16_to_double(h[r * cols + c]) / rms * bf16_to_double(gamma[c]);
+    }
+    return MOSS_O_OK;
+}
+
+int moss_oracle_rmsnorm_backward(const uint16_t *h, const uint16_t *gamma, const uint16_t *dy, const uint16_t *d_res,
+                                 double eps, int64_t rows, int64_t cols, double *d_h)
+{
+    if (!h || !gamma || !dy || !d_h || rows <= 0 || cols <= 0 || !(eps >= 0.0)) return MOSS_O_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; r++) {
+        double ss = 0.0;
+        for (int64_t c = 0; c < cols; c++) {
+            double v = bf16_to_double(h[r * cols + c]);
+            ss += v * v;
+        }
+        const double rms = sqrt(ss / (double)cols + eps);
+        double dot = 0.0;                                   /* sum_c g n */
+        for (int64_t c = 0; c < cols; c++) {
+            double g = bf16_to_double(dy[r * cols + c]) * bf16_to_double(gamma[c]);
+            dot += g * (bf16_to_double(h[r * cols + c]) / rms);
+        }
+        const double mean_gn = dot / (double)cols;
+        for (int64_t c = 0; c < cols; c++) {
+            double g = bf16_to_double(dy[r * cols + c]) * bf16_to_double(gamma[c]);
+            double n = bf16_to_double(h[r * cols + c]) / rms;
+            double res = d_res ? bf16_to_double(d_res[r * cols + c]) : 0.0;
+            d_h[r * cols + c] = res + (g - n * mean_gn) / rms;
+        }
+    }
+    return MOSS_O_OK;
+}
+
+/* ------------------------------------------------------------------ */
 /* The two schemes the paper compares two-level microscaling with (Sec. 3.1, Proof 1: per-tensor
  * quantization, Eq. 5, and per-group quantization, Eq. 6; the activation-SNR table of Sec. 4.5.2 uses
  * groups of 128): one FP32 scale per `group` consecutive elements of a row, s_g = max|X_g| / 448

@@ -79,6 +79,9 @@ def lib():
                                                C.c_void_p, C.c_void_p, C.c_float,
                                                C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.moss_oracle_row_norms.argtypes = [C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
+        L.moss_oracle_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_double, C.c_int64, C.c_int64, C.c_void_p]
+        L.moss_oracle_rmsnorm_backward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_int64, C.c_int64,
+                                                   C.c_void_p]
         L.moss_oracle_groupwise_fp8.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.moss_oracle_num_threads.restype = C.c_int
         _lib = L
@@ -219,6 +222,28 @@ def row_norms(q, e, s):
     e = None if e is None else _u8(e)
     out = np.empty(R, np.float64)
     _check(lib().moss_oracle_row_norms(R, K, _p(q), _p(e), float(s), _p(out)), "row_norms")
+    return out
+
+
+def rmsnorm(h_bits, gamma_bits, eps):
+    """y = h / sqrt(mean(h^2) + eps) * gamma over each row, in double, from BF16 bit arrays h [rows, cols], gamma [cols]."""
+    h = np.ascontiguousarray(h_bits, dtype=np.uint16); g = np.ascontiguousarray(gamma_bits, dtype=np.uint16)
+    rows, cols = h.shape
+    assert g.shape == (cols,)
+    y = np.empty((rows, cols), np.float64)
+    _check(lib().moss_oracle_rmsnorm(_p(h), _p(g), float(eps), rows, cols, _p(y)), "rmsnorm")
+    return y
+
+
+def rmsnorm_backward(h_bits, gamma_bits, dy_bits, d_res_bits, eps):
+    """d_h for the upstream gradient dy of rmsnorm(h), plus the residual-path gradient d_res (or None), in double."""
+    h = np.ascontiguousarray(h_bits, dtype=np.uint16); g = np.ascontiguousarray(gamma_bits, dtype=np.uint16)
+    dy = np.ascontiguousarray(dy_bits, dtype=np.uint16)
+    dr = None if d_res_bits is None else np.ascontiguousarray(d_res_bits, dtype=np.uint16)
+    rows, cols = h.shape
+    assert g.shape == (cols,) and dy.shape == h.shape and (dr is None or dr.shape == h.shape)
+    out = np.empty((rows, cols), np.float64)
+    _check(lib().moss_oracle_rmsnorm_backward(_p(h), _p(g), _p(dy), _p(dr), float(eps), rows, cols, _p(out)), "rmsnorm_backward")
     return out
 
 

@@ -25,6 +25,9 @@ int moss_oracle_row_norms(int64_t, int64_t, const uint8_t *, const uint8_t *, fl
 int moss_oracle_swiglu(const uint16_t *, const uint16_t *, int64_t, double *);
 int moss_oracle_swiglu_backward(const uint16_t *, const uint16_t *, const uint16_t *, int64_t, double *, double *);
 double moss_oracle_snr_db(const double *, const double *, int64_t);
+int moss_oracle_rmsnorm(const uint16_t *, const uint16_t *, double, int64_t, int64_t, double *);
+int moss_oracle_rmsnorm_backward(const uint16_t *, const uint16_t *, const uint16_t *, const uint16_t *, double, int64_t, int64_t, double *);
+int moss_oracle_groupwise_fp8(const uint16_t *, int64_t, int64_t, int64_t, uint8_t *, float *, double *);
 
 static uint64_t rs = 0x9E3779B97F4A7C15ull;
 static uint32_t rnd(void) { rs ^= rs << 13; rs ^= rs >> 7; rs ^= rs << 17; return (uint32_t)(rs >> 32); }
@@ -102,6 +105,22 @@ int main(void)
     for (int i = 0; i < 9; i++) { gt[i] = bf16_of((float)(i - 4) * 3.0f); up[i] = bf16_of((float)i * 0.5f); dh[i] = bf16_of(1e-3f * (float)(i + 1)); }
     CHECK(moss_oracle_swiglu(gt, up, 9, h) == 0 && moss_oracle_swiglu_backward(gt, up, dh, 9, dg, du) == 0);
     CHECK(moss_oracle_swiglu(gt, up, 0, h) == 0);
+    /* RMSNorm and the comparison quantizers on exactly sized buffers */
+    {
+        const int64_t r = 3, c = 48;
+        uint16_t *hh = malloc(sizeof(uint16_t) * r * c), *gg = malloc(sizeof(uint16_t) * c), *dd = malloc(sizeof(uint16_t) * r * c);
+        double *yy = malloc(sizeof(double) * r * c), *dq = malloc(sizeof(double) * r * c);
+        uint8_t *qq = malloc(r * c);
+        float *sc = malloc(sizeof(float) * r * c / 16);
+        for (int64_t i = 0; i < r * c; i++) { hh[i] = bf16_of(((float)(rnd() % 2001) - 1000.0f) / 300.0f); dd[i] = bf16_of(((float)(rnd() % 2001) - 1000.0f) * 1e-3f); }
+        for (int64_t i = 0; i < c; i++) gg[i] = bf16_of(1.0f + (float)(i % 5) * 0.1f);
+        CHECK(moss_oracle_rmsnorm(hh, gg, 1e-5, r, c, yy) == 0);
+        CHECK(moss_oracle_rmsnorm_backward(hh, gg, dd, NULL, 1e-5, r, c, yy) == 0);
+        CHECK(moss_oracle_rmsnorm_backward(hh, gg, dd, hh, 0.0, r, c, yy) == 0);
+        CHECK(moss_oracle_groupwise_fp8(hh, r, c, 16, qq, sc, dq) == 0 && moss_oracle_groupwise_fp8(hh, r, c, 0, qq, sc, dq) == 0);
+        CHECK(moss_oracle_groupwise_fp8(hh, r, c, 32, qq, NULL, dq) != 0);      /* 48 % 32 != 0: refused */
+        free(hh); free(gg); free(dd); free(yy); free(dq); free(qq); free(sc);
+    }
     double xs[3] = {3, 4, 0}, ds[3] = {3, 4, 1};
     CHECK(fabs(moss_oracle_snr_db(xs, ds, 3) - 13.979400086720377) < 1e-12);
     printf("oracle sanitizer run: ok\n");
