@@ -154,6 +154,33 @@ int moss_swiglu_bf16_backward(const void *gate, const void *up, const void *dh, 
                               void *stream);
 
 /* ---------------------------------------------------------------------------
+ * RMSNorm, the BF16 producer in front of the quantizers of the QKV and of the gate / up projections
+ * (non-linear layers stay in BF16, Sec. 4.1; as for SwiGLU above, the point is the maximum word that
+ * lets the quantizer of Sec. 3.1 skip its search pass).  Over each row of h [rows x cols]:
+ *      y = h / sqrt(mean(h^2) + eps) * gamma.
+ * Forward, optionally fused with the residual add in front of the norm: with delta != NULL,
+ * h = x + delta is rounded to BF16 and written to h_out, and the norm is taken over those rounded
+ * values; with delta == NULL, h = x (h_out is ignored).  y is rounded once to BF16 from an FP32
+ * evaluation (|y - exact| <= (1/2 + 2^-9) BF16 ulp); *y_absmax_bits receives max|y| as written.
+ *
+ * Backward, fused with the gradient that reaches h directly over the residual connection
+ * (d_res, NULL for none):
+ *      g = dy * gamma,  n = h / sqrt(mean(h^2) + eps),
+ *      d_h = d_res + (g - n * mean(g * n)) / sqrt(mean(h^2) + eps),
+ * rounded once to BF16, with its maximum word (d_h is the O projection's dY in a pre-norm block).
+ * The gradient of gamma is not produced (it never meets a quantizer).
+ *
+ * x, delta, h, h_out, y, dy, d_res, d_h: BF16 [rows x cols], row stride `ld` elements; gamma: BF16 [cols].
+ * Requirements: cols % 8 == 0, cols <= 16384 (a row is held in one workgroup's registers, else
+ * MOSS_ERR_UNSUPPORTED), ld >= cols, ld % 8 == 0, eps >= 0, 16-byte aligned pointers, finite inputs.
+ * The maximum words are device memory, written (not accumulated) by the call.                      */
+int moss_add_rmsnorm_bf16(const void *x, const void *delta, const void *gamma, float eps, int64_t rows, int64_t cols,
+                          int64_t ld, void *h_out, void *y, uint32_t *y_absmax_bits, void *stream);
+int moss_rmsnorm_bf16_backward(const void *h, const void *gamma, const void *dy, const void *d_res, float eps,
+                               int64_t rows, int64_t cols, int64_t ld, void *d_h, uint32_t *d_h_absmax_bits,
+                               void *stream);
+
+/* ---------------------------------------------------------------------------
  * Per-tensor FP8 weights with automatic scaling  (paper Sec. 3.2, Eq. 10 and the
  * interval re-scaling of its last paragraph; AdamW as in Sec. 2.2 Eq. 1; App. C).
  *

@@ -65,6 +65,8 @@ def load():
     L.moss_quant_act_2level_given_max.argtypes = [vp, i64, i64, i64, u32, vp, vp, vp, vp, vp, vp, vp]
     L.moss_swiglu_bf16.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
     L.moss_swiglu_bf16_backward.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp]
+    L.moss_add_rmsnorm_bf16.argtypes = [vp, vp, vp, C.c_float, i64, i64, i64, vp, vp, vp, vp]
+    L.moss_rmsnorm_bf16_backward.argtypes = [vp, vp, vp, vp, C.c_float, i64, i64, i64, vp, vp, vp]
     L.moss_quant_set_poll_limit.restype = None
     L.moss_quant_set_poll_limit.argtypes = [u32]
     L.moss_weight_workspace_bytes.restype = sz
@@ -216,6 +218,46 @@ def swiglu_bf16_backward(gate, up, dh, d_gate=None, d_up=None, d_gate_absmax_bit
                                      _ptr(d_gate_absmax_bits), _ptr(d_up_absmax_bits), _stream())
     _check(rc, "moss_swiglu_bf16_backward")
     return d_gate, d_up, d_gate_absmax_bits, d_up_absmax_bits
+
+
+def add_rmsnorm_bf16(x, gamma, eps, delta=None, h=None, y=None, absmax_bits=None):
+    """(h, y, max word): h = x + delta (x itself if delta is None), y = rmsnorm(h) * gamma, max|y| as BF16 bits."""
+    import torch
+    L = load()
+    rows, cols = x.shape
+    ld = x.stride(0)
+    for t in (x, delta):
+        assert t is None or (t.dtype == torch.bfloat16 and t.is_cuda and t.stride(1) == 1 and t.shape == x.shape and t.stride(0) == ld)
+    assert gamma.dtype == torch.bfloat16 and gamma.is_contiguous() and gamma.shape == (cols,)
+    mk = lambda: torch.empty_strided((rows, cols), (ld, 1), dtype=torch.bfloat16, device=x.device)
+    if delta is not None and h is None:
+        h = mk()
+    y = mk() if y is None else y
+    if absmax_bits is None:
+        absmax_bits = torch.empty(1, dtype=torch.int32, device=x.device)
+    rc = L.moss_add_rmsnorm_bf16(_ptr(x), _ptr(delta), _ptr(gamma), float(eps), rows, cols, ld, _ptr(h) if delta is not None else None,
+                                 _ptr(y), _ptr(absmax_bits), _stream())
+    _check(rc, "moss_add_rmsnorm_bf16")
+    return (h if delta is not None else x), y, absmax_bits
+
+
+def rmsnorm_bf16_backward(h, gamma, dy, eps, d_res=None, d_h=None, absmax_bits=None):
+    """(d_h, max word) for the upstream gradient dy of rmsnorm(h) * gamma, plus the residual-path gradient d_res."""
+    import torch
+    L = load()
+    rows, cols = h.shape
+    ld = h.stride(0)
+    for t in (h, dy, d_res):
+        assert t is None or (t.dtype == torch.bfloat16 and t.is_cuda and t.stride(1) == 1 and t.shape == h.shape and t.stride(0) == ld)
+    assert gamma.dtype == torch.bfloat16 and gamma.is_contiguous() and gamma.shape == (cols,)
+    if d_h is None:
+        d_h = torch.empty_strided((rows, cols), (ld, 1), dtype=torch.bfloat16, device=h.device)
+    if absmax_bits is None:
+        absmax_bits = torch.empty(1, dtype=torch.int32, device=h.device)
+    rc = L.moss_rmsnorm_bf16_backward(_ptr(h), _ptr(gamma), _ptr(dy), _ptr(d_res), float(eps), rows, cols, ld, _ptr(d_h),
+                                      _ptr(absmax_bits), _stream())
+    _check(rc, "moss_rmsnorm_bf16_backward")
+    return d_h, absmax_bits
 
 
 def quant_set_poll_limit(polls):

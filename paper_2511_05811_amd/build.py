@@ -7,7 +7,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG), "include")
 LIB = os.path.join(PKG, "libmoss_hip.so")
-SOURCES = ["moss_api.hip", "moss_quant.hip", "moss_weight.hip", "moss_gemm.hip", "moss_gemm_big.hip", "moss_swiglu.hip"]
+SOURCES = ["moss_api.hip", "moss_quant.hip", "moss_weight.hip", "moss_gemm.hip", "moss_gemm_big.hip", "moss_swiglu.hip", "moss_rmsnorm.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-ffp-contract=off",                      # numerically specified kernels: no FMA contraction

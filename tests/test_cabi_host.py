@@ -93,6 +93,22 @@ def test_producer_argument_validation(L):
     assert b(mg=FAKE, mu=FAKE) == 5                       # one word for two maxima
 
 
+def test_rmsnorm_argument_validation(L):
+    import ctypes
+    f = lambda x=FAKE, d=None, g=FAKE, eps=1e-5, rows=4, cols=64, ld=64, h=None, y=FAKE, m=FAKE: \
+        L.moss_add_rmsnorm_bf16(x, d, g, ctypes.c_float(eps), rows, cols, ld, h, y, m, None)
+    assert f(x=None) == 1 and f(m=None) == 1
+    assert f(d=FAKE, h=None) == 1                          # a residual sum needs somewhere to go
+    assert f(cols=12) == 2 and f(rows=0) == 2 and f(ld=32) == 2 and f(eps=-1.0) == 2
+    assert f(cols=16384 + 8, ld=16384 + 8) == 5            # a row has to fit one workgroup's registers
+    assert f(ld=68) == 3 and f(y=FAKE + 8) == 3 and f(m=FAKE + 2) == 3
+    b = lambda h=FAKE, g=FAKE, dy=FAKE, dr=None, cols=64, dh=FAKE, m=FAKE: \
+        L.moss_rmsnorm_bf16_backward(h, g, dy, dr, ctypes.c_float(1e-5), 4, cols, 64, dh, m, None)
+    assert b(dy=None) == 1 and b(m=None) == 1
+    assert b(cols=60) == 2
+    assert b(dr=FAKE + 4) == 3 and b(dh=FAKE + 2) == 3
+
+
 def test_weight_argument_validation(L):
     args = moss.AdamWArgs(3e-4, 0.9, 0.95, 1e-8, 0.1, 0.1, 0.05, 0.1, 0.05, 1.0, 500, 1)
     big = 1 << 20
