@@ -13,26 +13,35 @@ linear layers differ:
 
 Q, K and V are one fused hidden -> 3 hidden linear; gate and up are separate linears.
 
-SwiGLU is the library's BF16 kernel in both arms (`swiglu="fused"`, the default) or torch's
-silu and mul (`swiglu="torch"`).  In the "moss" arm the fused kernel also hands the maximum of
-what it wrote (h forward, d_gate and d_up backward) to the quantizer of the linear that consumes
-it, which then reads that tensor once instead of twice.
+SwiGLU and RMSNorm (the second one fused with the residual add in front of it, its backward with the
+gradient of the residual path) are the library's BF16 kernels in both arms (`swiglu="fused"`,
+`norm="fused"`, the defaults) or torch's operations (`"torch"`).  In the "moss" arm the fused kernels
+also hand the maximum of what they wrote to the quantizer of the linear that consumes it, which
+then needs no search pass: the inputs of all five linears but the attention output, and every
+dY but that of the QKV projection (it comes out of torch's attention backward) and of the down
+projection (the upstream gradient).
 """
 
 
 class _MaxWords:
-    """Side channel from a producer to the quantizer of the tensor it wrote: the device word that
-    holds the tensor's maximum, keyed by the tensor's storage."""
+    """Side channel from a producer to the quantizers of the tensor it wrote: the device word that holds the
+    tensor's maximum, keyed by the tensor's storage.  A word stays valid for every consumer of the tensor (the
+    normalised hidden state feeds two projections) as long as nothing has written to the tensor since: its
+    version counter is part of the entry."""
 
     def __init__(self):
         self.words = {}
+        self.used = 0
 
     def put(self, tensor, word):
-        self.words[tensor.data_ptr()] = (tuple(tensor.shape), word)
+        self.words[tensor.data_ptr()] = (tuple(tensor.shape), tensor._version, word)
 
     def take(self, tensor):
-        e = self.words.pop(tensor.data_ptr(), None)
-        return e[1] if e is not None and e[0] == tuple(tensor.shape) else None
+        e = self.words.get(tensor.data_ptr())
+        if e is None or e[0] != tuple(tensor.shape) or e[1] != tensor._version:
+            return None
+        self.used += 1
+        return e[2]
 
     def clear(self):
         self.words.clear()
@@ -128,6 +137,47 @@ def _swiglu_fn(moss, torch):
     return Fn
 
 
+def _rmsnorm_fns(moss, torch, eps):
+    """RMSNorm on the library's kernels: `plain(x, gamma, words)` -> y, and `added(x, delta, gamma, words)` ->
+    (h = x + delta, y = norm(h)).  Backward adds the gradient that reaches h over the residual connection inside the
+    kernel.  With `words` the maxima of y (forward) and of the gradient (backward) go to the quantizers."""
+    class Plain(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, x, gamma, words):
+            x = x.contiguous()
+            _, y, word = moss.add_rmsnorm_bf16(x, gamma, eps)
+            ctx.save_for_backward(x, gamma)
+            ctx.words = words
+            if words is not None:
+                words.put(y, word)
+            return y
+
+        @staticmethod
+        def backward(ctx, dy):
+            x, gamma = ctx.saved_tensors
+            d, word = moss.rmsnorm_bf16_backward(x, gamma, dy.contiguous(), eps)
+            return d, None, None
+
+    class Added(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, x, delta, gamma, words):
+            h, y, word = moss.add_rmsnorm_bf16(x.contiguous(), gamma, eps, delta=delta.contiguous())
+            ctx.save_for_backward(h, gamma)
+            ctx.words = words
+            if words is not None:
+                words.put(y, word)
+            return h, y
+
+        @staticmethod
+        def backward(ctx, dh, dy):
+            h, gamma = ctx.saved_tensors
+            d, word = moss.rmsnorm_bf16_backward(h, gamma, dy.contiguous(), eps, d_res=dh.contiguous())
+            if ctx.words is not None:
+                ctx.words.put(d, word)          # d is the O projection's dY
+            return d, d, None, None
+    return Plain, Added
+
+
 class _Bf16Linear:
     def __init__(self, torch, k, n, gen, dev):
         self.master = torch.nn.Parameter(torch.randn((n, k), generator=gen, device=dev, dtype=torch.float32) * 0.02)
@@ -156,11 +206,13 @@ def _bf16_linear_fn(torch):
 class DecoderBlock:
     """hidden -> attention -> SwiGLU FFN, pre-norm, as in LLaMA."""
 
-    def __init__(self, moss, torch, arm, batch, seq, hidden, heads, ffn, seed=5, swiglu="fused"):
-        assert arm in ("moss", "bf16") and hidden % heads == 0 and swiglu in ("fused", "torch")
+    def __init__(self, moss, torch, arm, batch, seq, hidden, heads, ffn, seed=5, swiglu="fused", norm="fused"):
+        assert arm in ("moss", "bf16") and hidden % heads == 0 and swiglu in ("fused", "torch") and norm in ("fused", "torch")
         self.torch, self.moss, self.arm = torch, moss, arm
-        self.words = _MaxWords() if (arm == "moss" and swiglu == "fused") else None
+        self.words = _MaxWords() if (arm == "moss" and (swiglu == "fused" or norm == "fused")) else None
         self.swiglu = _swiglu_fn(moss, torch) if swiglu == "fused" else None
+        self.swiglu_words = self.words if swiglu == "fused" else None
+        self.norms = _rmsnorm_fns(moss, torch, 1e-5) if norm == "fused" else None
         self.batch, self.seq, self.hidden, self.heads, self.ffn = batch, seq, hidden, heads, ffn
         dev = torch.device("cuda:0")
         gen = torch.Generator(device=dev)
@@ -197,17 +249,22 @@ class DecoderBlock:
         B, S, H, nh = self.batch, self.seq, self.hidden, self.heads
         T, hd = B * S, H // nh
         lin, fn = self.lin, self.fn
-        a = F.rms_norm(x, (H,), self.g1, 1e-5)
-        qkv = fn.apply(a.view(T, H), lin["qkv"]).view(B, S, 3, nh, hd)
+        xs = x.view(T, H)
+        a = self.norms[0].apply(xs, self.g1, self.words) if self.norms else F.rms_norm(xs, (H,), self.g1, 1e-5)
+        qkv = fn.apply(a, lin["qkv"]).view(B, S, 3, nh, hd)
         q, k, v = (qkv[:, :, i].transpose(1, 2) for i in range(3))
         att = F.scaled_dot_product_attention(self._rope(q), self._rope(k), v, is_causal=True)
-        h = x + fn.apply(att.transpose(1, 2).reshape(T, H), lin["o"]).view(B, S, H)
-        b = F.rms_norm(h, (H,), self.g2, 1e-5).view(T, H)
+        o = fn.apply(att.transpose(1, 2).reshape(T, H), lin["o"])
+        if self.norms:
+            h, b = self.norms[1].apply(xs, o, self.g2, self.words)       # residual add and norm in one kernel
+        else:
+            h = xs + o
+            b = F.rms_norm(h, (H,), self.g2, 1e-5)
         if self.swiglu is not None:
-            f = self.swiglu.apply(fn.apply(b, lin["gate"]), fn.apply(b, lin["up"]), self.words)
+            f = self.swiglu.apply(fn.apply(b, lin["gate"]), fn.apply(b, lin["up"]), self.swiglu_words)
         else:
             f = F.silu(fn.apply(b, lin["gate"])) * fn.apply(b, lin["up"])
-        return h + fn.apply(f, lin["down"]).view(B, S, H)
+        return (h + fn.apply(f, lin["down"])).view(B, S, H)
 
     def train_step(self):
         """forward, backward with the fixed upstream gradient, optimizer step on the five weights"""

@@ -152,16 +152,17 @@ def gemm(moss, torch, small=False):
 
 def block(moss, torch, small=False):
     """One training step (forward, backward, optimizer) of one LLaMA-7B-shaped decoder block at batch 2 x
-    sequence 4096.  Both arms share the BF16 scaffolding (torch RMSNorm, rotary embedding, causal
-    scaled-dot-product attention, SwiGLU, residuals); only the five linears and their optimizer differ."""
+    sequence 4096.  Both arms share the BF16 scaffolding (RMSNorm, rotary embedding, causal scaled-dot-product
+    attention, SwiGLU, residuals); only the five linears and their optimizer differ."""
     import time
     from . import block as blk
     sz = blk.sizes_small() if small else blk.sizes_7b()
     tokens = sz["batch"] * sz["seq"]
     out = {"table": "block", "sizes": sz, "tokens": tokens, "arms": {}}
     steps, warm = (3, 2) if small else (8, 3)
-    for arm, swiglu in (("moss", "fused"), ("bf16", "fused"), ("moss", "torch"), ("bf16", "torch")):
-        b = blk.DecoderBlock(moss, torch, arm, swiglu=swiglu, **sz)
+    for arm, swiglu, norm in (("moss", "fused", "fused"), ("bf16", "fused", "fused"), ("moss", "fused", "torch"), ("bf16", "fused", "torch"),
+                              ("moss", "torch", "torch"), ("bf16", "torch", "torch")):
+        b = blk.DecoderBlock(moss, torch, arm, swiglu=swiglu, norm=norm, **sz)
         for _ in range(warm):
             b.train_step()
         torch.cuda.synchronize()
@@ -170,16 +171,16 @@ def block(moss, torch, small=False):
             b.train_step()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / steps * 1e3
-        key = arm if swiglu == "fused" else arm + "_torch_swiglu"
+        key = arm + ("" if norm == "fused" else "_torch_norm") + ("" if swiglu == "fused" else "_torch_swiglu")
         out["arms"][key] = {"ms_per_step": round(ms, 3), "tokens_per_s": round(tokens / ms * 1e3, 1)}
         del b
         torch.cuda.empty_cache()
     out["speedup_moss_over_bf16"] = round(out["arms"]["bf16"]["ms_per_step"] / out["arms"]["moss"]["ms_per_step"], 3)
     out["linear_tflop_per_step"] = round(blk.linear_flops(sz["batch"], sz["seq"], sz["hidden"], sz["ffn"]) / 1e12, 3)
     out["attention_tflop_per_step"] = round(blk.attention_flops(sz["batch"], sz["seq"], sz["hidden"]) / 1e12, 3)
-    out["note"] = ("bf16 arm: torch matmul (vendor BF16 GEMM) and torch fused AdamW; scaffolding identical in both arms (SwiGLU: the "
-                   "library's BF16 kernel, which in the moss arm also hands the tensor maxima to the quantizers; *_torch_swiglu: "
-                   "torch silu and mul in both arms); "
+    out["note"] = ("bf16 arm: torch matmul (vendor BF16 GEMM) and torch fused AdamW; scaffolding identical in both arms (SwiGLU and "
+                   "RMSNorm + residual add: the library's BF16 kernels, which in the moss arm also hand the tensor maxima to the "
+                   "quantizers; *_torch_norm: torch rms_norm and add in both arms; *_torch_swiglu: torch silu and mul as well); "
                    "paper (8 x H800, full 7B model): 1.34x over BF16, context only")
     return out
 

@@ -59,11 +59,13 @@ def test_decoder_block_arms_agree_on_a_small_block():
         assert rel(a.lin[name].dw, b.lin[name].dw) < 0.25, name
     # the library's SwiGLU (which also hands the tensor maxima to the quantizers) against torch's silu and mul:
     # the same step up to BF16 rounding of the SwiGLU outputs
-    c = blk.DecoderBlock(moss, torch, "moss", swiglu="torch", **sz)
+    # ... and its RMSNorm kernels against torch's rms_norm and add
+    c = blk.DecoderBlock(moss, torch, "moss", swiglu="torch", norm="torch", **sz)
     oc, gc = c.train_step()
     torch.cuda.synchronize()
     assert rel(oa, oc) < 0.01 and rel(ga, gc) < 0.02
-    assert a.words is not None and not a.words.words        # every maximum that was handed over was consumed
+    # the maxima handed over were used: X of qkv, gate, up, down and dY of o, gate, up
+    assert a.words is not None and a.words.used == 7 and c.words is None
     res = microbench.block(moss, torch, small=True)
     assert res["arms"]["moss"]["tokens_per_s"] > 0 and res["arms"]["bf16"]["tokens_per_s"] > 0
-    assert res["arms"]["moss_torch_swiglu"]["tokens_per_s"] > 0
+    assert res["arms"]["moss_torch_norm"]["tokens_per_s"] > 0 and res["arms"]["moss_torch_norm_torch_swiglu"]["tokens_per_s"] > 0
