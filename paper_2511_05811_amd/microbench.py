@@ -8,6 +8,7 @@
                                                          # FP8 path vs BF16 GEMMs (attention, norms, SwiGLU: BF16 torch ops)
     python -m paper_2511_05811_amd.microbench producer  # SwiGLU that also hands the tensor maximum to the quantizer (Sec. 3.1,
                                                          # Eq. 2 without the search): one pass over h instead of two
+    python -m paper_2511_05811_amd.microbench quant     # the activation quantizer alone, per shape and grouping, beside a plain copy
     python -m paper_2511_05811_amd.microbench limits    # what the machine allows: GEMM rate and shader clock by operand
                                                          # content (power limit), plain device-copy bandwidth
 
@@ -227,6 +228,59 @@ def producer(moss, torch, small=False):
                     "reads h twice at this size (172 MiB), the one given the maximum once"}
 
 
+def quant(moss, torch, small=False):
+    """The activation quantizer alone (config 2 of the benchmark and the 7B activation widths): every call after a
+    512 MiB fill that leaves the caches cold and full of dirty lines, timed between events; GB/s of the
+    algorithmic bytes (2 B read + 1.03125 B written per element and grouping) and of the bytes actually moved
+    (tensors above 64 MiB are read twice by the searching entry point).  For scale: a plain device copy of the
+    same tensor (2 B read + 2 B written per element)."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(46)
+    u8 = torch.uint8
+    shapes = [(256, 512)] if small else [(8192, 4096), (8192, 11008), (8192, 12288)]
+    flush = torch.empty((8 if small else 512) << 20, dtype=u8, device=dev)
+    reps = 3 if small else 10
+    rows_out = []
+
+    def timed(fn):
+        ts = []
+        for i in range(reps + 2):
+            flush.fill_(i & 0xFF)
+            e0, e1 = _events(torch)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ts = sorted(ts[2:])
+        return ts[len(ts) // 2]
+    for rows, cols in shapes:
+        n = rows * cols
+        x = (torch.randn((rows, cols), generator=gen, device=dev, dtype=torch.float32)).to(torch.bfloat16)
+        out = dict(q_row=torch.empty((rows, cols), dtype=u8, device=dev), e_row=torch.empty((rows, cols // 32), dtype=u8, device=dev),
+                   q_col=torch.empty((cols, rows), dtype=u8, device=dev), e_col=torch.empty((cols, rows // 32), dtype=u8, device=dev),
+                   s=torch.empty(1, dtype=torch.float32, device=dev))
+        ws = torch.empty(max(16, moss.load().moss_quant_workspace_bytes(rows, cols, 3)), dtype=u8, device=dev)
+        word = (x.view(torch.int16).to(torch.int32) & 0x7FFF).max().to(torch.int32).reshape(1)
+        y = torch.empty_like(x)
+        copy_ms = timed(lambda: y.copy_(x))
+        for name, flags in (("row", moss.MOSS_Q_ROW), ("col", moss.MOSS_Q_COL), ("both", moss.MOSS_Q_ROW | moss.MOSS_Q_COL)):
+            bpe = 2.0 + (2.0625 if name == "both" else 1.03125)
+            twice = n * 2 > (64 << 20)
+            ms = timed(lambda: moss.quant_act_2level(x, flags, out=out, workspace=ws))
+            ms_given = timed(lambda: moss.quant_act_2level_given_max(x, word, flags, out=out))
+            rows_out.append({"rows": rows, "cols": cols, "groupings": name, "searching_ms": round(ms, 4),
+                             "searching_algorithmic_gbs": round(n * bpe / ms / 1e6, 1),
+                             "searching_moved_gbs": round(n * (bpe + (2.0 if twice else 0.0)) / ms / 1e6, 1),
+                             "given_max_ms": round(ms_given, 4), "given_max_gbs": round(n * bpe / ms_given / 1e6, 1),
+                             "device_copy_ms": round(copy_ms, 4), "device_copy_gbs": round(n * 4.0 / copy_ms / 1e6, 1)})
+        del x, y, out
+    return {"table": "quant", "unit": "ms", "rows": rows_out,
+            "note": "event-bracketed single calls, each after a 512 MiB fill; the searching entry point is one launch up to 64 MiB "
+                    "(X read once) and two launches above (X read twice)"}
+
+
 class _ClockPoller:
     """Samples the shader clock with `rocm-smi --showclocks` (a child process that only reads sysfs)
     while the GPU works."""
@@ -307,7 +361,7 @@ def limits(moss, torch, small=False):
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["scaling", "gemm", "limits", "block", "producer"])
+    ap.add_argument("table", choices=["scaling", "gemm", "limits", "block", "producer", "quant"])
     ap.add_argument("--small", action="store_true", help="tiny shapes (used by the tests)")
     a = ap.parse_args(argv)
     import torch
@@ -315,7 +369,7 @@ def main(argv=None):
     if not torch.cuda.is_available():
         print("microbench needs the MI355X", file=sys.stderr)
         return 2
-    res = {"scaling": scaling, "gemm": gemm, "limits": limits, "block": block, "producer": producer}[a.table](moss, torch, a.small)
+    res = {"scaling": scaling, "gemm": gemm, "limits": limits, "block": block, "producer": producer, "quant": quant}[a.table](moss, torch, a.small)
     print(json.dumps(res))
     return 0
 

@@ -29,6 +29,11 @@ def test_producer_table_small():
     assert t["swiglu_with_max_ms"] > 0 and t["quant_given_max_ms"] > 0 and t["chain_fused_ms"] > 0
 
 
+def test_quant_table_small():
+    rows = microbench.quant(moss, torch, small=True)["rows"]
+    assert len(rows) == 3 and all(r["searching_ms"] > 0 and r["given_max_ms"] > 0 and r["device_copy_ms"] > 0 for r in rows)
+
+
 def test_limits_table_small():
     res = microbench.limits(moss, torch, small=True)
     assert len(res["gemm_by_operand_content"]) == 3 and all(r["tflops"] > 0 for r in res["gemm_by_operand_content"])
