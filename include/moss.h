@@ -272,6 +272,8 @@ int moss_weight_autoscale_cast(float *w, float *m, float *v, const void *g, int 
  * applied by the matrix instruction itself.
  * Requirements: K % 32 == 0; ld_out >= N; accumulate only with MOSS_DT_F32.
  * ------------------------------------------------------------------------- */
+/* The GEMM needs no scratch today: moss_gemm_workspace_bytes returns 0 and `workspace` / `workspace_bytes` are
+ * not looked at (pass NULL and 0); the arguments are reserved for a split-K variant. */
 size_t moss_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 int moss_gemm_fp8_mx(int64_t M, int64_t N, int64_t K,

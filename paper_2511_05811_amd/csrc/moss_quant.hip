@@ -413,7 +413,9 @@ __device__ __forceinline__ void tile_codes(const uint4 (&raw)[8], const float (&
 #pragma unroll
                 for (int j = 0; j < 8; j++) y[j] = clamp448(scaled<FUSED>(x[k][j], rf[it], eb, inv_s));
                 const uint2 out = make_uint2(cvt_hi(y[2], y[3], cvt_lo_fresh(y[0], y[1])), cvt_hi(y[6], y[7], cvt_lo_fresh(y[4], y[5])));
-                if (FULL || it < n_ok) st_stream8(q_row_tile + (q_row_off + (uint32_t)it * cols), out);
+                // (codes are stored through the caches: the GEMM that follows reads them, and inside a training step this
+                // measured 2 % faster for the quantizer than streaming stores; X itself is streamed)
+                if (FULL || it < n_ok) *reinterpret_cast<uint2 *>(q_row_tile + (q_row_off + (uint32_t)it * cols)) = out;
             }
         }
         if (!COL) continue;
@@ -591,7 +593,7 @@ __device__ __forceinline__ bool quant_tile_body(const uint4 (&raw)[8], const Til
             const int idx = tid + k * kQuantThreads, c = idx >> 3, piece = idx & 7;
             if (FULL || (c0 + c < cols && r0 + piece * 16 < rows)) {
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(&lds.tt[c][piece * 16]);
-                st_stream16(q_col_tile + ((uint32_t)c * (uint32_t)rows + (uint32_t)piece * 16), make_uint4(src[0], src[1], src[2], src[3]));
+                *reinterpret_cast<uint4 *>(q_col_tile + ((uint32_t)c * (uint32_t)rows + (uint32_t)piece * 16)) = make_uint4(src[0], src[1], src[2], src[3]);
             }
         }
     }

@@ -104,7 +104,7 @@ def test_one_hot_operands_pin_the_lane_and_scale_mapping(oracle):
 
 
 @pytest.mark.parametrize("shape,ld", [((70, 52, 192), 64),          # general kernel
-                                      ((600, 1000, 512), 1004),     # large-tile kernel, ld_out % 8 != 0: scalar stores
+                                      ((600, 1000, 512), 1004),     # ld_out % 8 != 0: the general kernel (the large-tile epilogue stores whole 16-byte pieces)
                                       ((1024, 776, 640), 784)])     # large-tile kernel, vector stores, ragged N
 def test_fp32_accumulate_and_padded_output(oracle, shape, ld):
     M, N, K = shape
