@@ -93,7 +93,7 @@ def adamw_args(moss, t):
 
 def run_step(wl, moss, torch, t, rec):
     """One pass of the whole path.  rec(kind) returns a context that brackets a call with events."""
-    both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL
+    both = moss.MOSS_Q_ROW | moss.MOSS_Q_COL | moss.MOSS_WS_KEPT      # (ws_q: zero-filled above, used by these calls only)
     f32 = torch.float32
     for L in wl.layers:
         with rec("quant"):

@@ -80,6 +80,12 @@ int moss_device_cu_count(void);
 #define MOSS_Q_COL 2u
 #define MOSS_EXP_NEAREST 0u
 #define MOSS_EXP_CEIL 4u
+/* Optional promise about `workspace` (moss_quant_act_2level only): it was zero-filled before its first use
+ * and since then nothing but completed calls of moss_quant_act_2level has written to it.  The one-launch
+ * path (tensors of up to 64 MiB) then skips the small launch that clears its meeting words -- the kernel
+ * leaves them at zero itself.  Without the flag the workspace's contents need not be initialised.  A wrong
+ * promise gives a wrong global scale or a slow call, never an access out of bounds or a hang.           */
+#define MOSS_WS_KEPT 8u
 
 size_t moss_quant_workspace_bytes(int64_t rows, int64_t cols, unsigned flags);
 
@@ -95,7 +101,9 @@ int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t cols, int64_
  * (the quantizer's scratch does not grow with the shape, so every accepted shape fits); MOSS_ERR_HIP
  * if the array's address cannot be resolved.  The first call on a device resolves that address (a host
  * query, make it outside a capture).  All calls on one GPU share the one array: calls that overlap on a
- * GPU (different streams, different threads) race; order them on one stream.                      */
+ * GPU (different streams, different threads) race; order them on one stream.  The array is zero when
+ * the library is loaded and every kernel that uses its meeting words clears them before it ends, so a
+ * tensor of up to 64 MiB takes exactly one launch here.  MOSS_WS_KEPT is accepted and has no effect.  */
 int moss_quant_act_2level_noalloc(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
                                   uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
                                   float *s_global, void *stream);

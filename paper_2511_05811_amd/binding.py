@@ -13,6 +13,7 @@ _lib = None
 MOSS_DT_BF16, MOSS_DT_F32 = 0, 1
 MOSS_Q_ROW, MOSS_Q_COL = 1, 2
 MOSS_EXP_NEAREST, MOSS_EXP_CEIL = 0, 4
+MOSS_WS_KEPT = 8
 MOSS_WSTATE_STEP_MISMATCH = 1
 
 

@@ -66,7 +66,7 @@ class _MossLinear:
         self.wq_t = torch.empty((k, n), dtype=u8, device=dev)
         lib = moss.load()
         self.ws_w = torch.empty(max(16, lib.moss_weight_workspace_bytes(n, k)), dtype=u8, device=dev)
-        self.ws_q = torch.empty(max(16, lib.moss_quant_workspace_bytes(tokens, max(k, n), 3)), dtype=u8, device=dev)
+        self.ws_q = torch.zeros(max(16, lib.moss_quant_workspace_bytes(tokens, max(k, n), 3)), dtype=u8, device=dev)
         moss.weight_autoscale_init(self.w, self.state, wq=self.wq, wq_t=self.wq_t, workspace=self.ws_w)
         self.s_w = self.state[4:8].view(f32)
 
@@ -92,7 +92,7 @@ def _moss_linear_fn(torch):
             if word is not None:
                 moss.quant_act_2level_given_max(x, word, both, out=layer.qx)
             else:
-                moss.quant_act_2level(x, both, out=layer.qx, workspace=layer.ws_q)
+                moss.quant_act_2level(x, both | moss.MOSS_WS_KEPT, out=layer.qx, workspace=layer.ws_q)
             ctx.layer = layer
             return moss.gemm_fp8_mx(layer.qx["q_row"], layer.qx["e_row"], layer.qx["s"], layer.wq, None, layer.s_w)
 
@@ -106,7 +106,7 @@ def _moss_linear_fn(torch):
             if word is not None:
                 moss.quant_act_2level_given_max(dy, word, both, out=layer.qdy)
             else:
-                moss.quant_act_2level(dy, both, out=layer.qdy, workspace=layer.ws_q)
+                moss.quant_act_2level(dy, both | moss.MOSS_WS_KEPT, out=layer.qdy, workspace=layer.ws_q)
             dx = moss.gemm_fp8_mx(layer.qdy["q_row"], layer.qdy["e_row"], layer.qdy["s"], layer.wq_t, None, layer.s_w)
             moss.gemm_fp8_mx(layer.qdy["q_col"], layer.qdy["e_col"], layer.qdy["s"], layer.qx["q_col"], layer.qx["e_col"],
                              layer.qx["s"], out=layer.dw, out_dtype=torch.float32)

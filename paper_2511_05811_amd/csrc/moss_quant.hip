@@ -668,19 +668,25 @@ __global__ __launch_bounds__(kQuantThreads, 4) void k_quant_tile(const uint16_t 
 // here.  Everything that travels is a single word that carries its own validity:
 //   1. a workgroup merges its maximum into its group's word (atomic max) and only then -- the
 //      second atomic's operand depends on the first one's return value -- counts itself in;
-//   2. the workgroup that completes a group's count reads the group's word (all merges into it
+//   2. the workgroup that completes a group's count takes the group's word (all merges into it
 //      were performed before their senders counted in), merges it into the global word and
 //      counts the group in the same way;
-//   3. the workgroup that completes the count of groups reads the global word and publishes
+//   3. the workgroup that completes the count of groups takes the global word and publishes
 //      0x80000000 | maximum in one flag word per group, which the group's members poll.
 // The poll is bounded: a workgroup that does not see its flag within poll_limit polls (the grid
 // was not co-resident after all) computes the global maximum from X by itself, so every wave
 // ends whatever the scheduler does, and the outputs are the same either way.
+//
+// The words start at zero and the kernel leaves them at zero: whoever completes a count is the
+// last user of that count and of the maximum beside it and clears both; a flag is cleared by
+// the last of its group's members and its publisher to be done with it (one more count per
+// group, taken off the critical path: its result is looked at when the workgroup's tiles are
+// finished).  A caller whose words are known to be zero can therefore skip the clearing launch.
 constexpr int kKeep = 4;
 constexpr uint32_t kPollLimit = 1u << 15;
 constexpr int kSyncGroups = 8;
 constexpr int kSyncStride = 32;                                    // words: every word on a 128-byte line of its own
-constexpr int kSyncWords = (3 * kSyncGroups + 2) * kSyncStride;    // group maxima, group counts, flags, global max, global count
+constexpr int kSyncWords = (4 * kSyncGroups + 2) * kSyncStride;    // group maxima, group counts, flags, flag users, global max, global count
 
 __global__ void k_quant_sync_reset(uint32_t *sync)
 {
@@ -743,23 +749,36 @@ __global__ __launch_bounds__(kQuantThreads, 2) void k_quant_persist(const uint16
         m = c > m ? c : m;
     }
     // meeting point
+    uint32_t members = 0, my_use = 0;        // (thread 0's)
     m = wave_max_u32(m);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 1; i < kQuantThreads / kWave; i++) m = red[i] > m ? red[i] : m;
         uint32_t *grp_max = sync, *grp_cnt = sync + kSyncGroups * kSyncStride, *flags = sync + 2 * kSyncGroups * kSyncStride;
-        uint32_t *all_max = sync + 3 * kSyncGroups * kSyncStride, *all_cnt = all_max + kSyncStride;
+        uint32_t *users = sync + 3 * kSyncGroups * kSyncStride;
+        uint32_t *all_max = sync + 4 * kSyncGroups * kSyncStride, *all_cnt = all_max + kSyncStride;
         const int grp = first % kSyncGroups, n_grp = G < kSyncGroups ? G : kSyncGroups;
-        const uint32_t members = (uint32_t)((G - grp + kSyncGroups - 1) / kSyncGroups);
+        members = (uint32_t)((G - grp + kSyncGroups - 1) / kSyncGroups);
         uint32_t old = atomicMax(&grp_max[grp * kSyncStride], m);
         if (atomicAdd(&grp_cnt[grp * kSyncStride], after_value(1u, old)) == members - 1) {
-            const uint32_t gm = atomicMax(&grp_max[grp * kSyncStride], 0u);     // an atomic read of the group's word
+            const uint32_t gm = atomicExch(&grp_max[grp * kSyncStride], 0u);    // the group's maximum; word and count left at zero
+            __hip_atomic_store(&grp_cnt[grp * kSyncStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             old = atomicMax(all_max, gm);
             if (atomicAdd(all_cnt, after_value(1u, old)) == (uint32_t)n_grp - 1) {
-                const uint32_t am = atomicMax(all_max, 0u);
-                for (int i = 0; i < n_grp; i++)
-                    __hip_atomic_store(&flags[i * kSyncStride], 0x80000000u | am, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t am = atomicExch(all_max, 0u);
+                __hip_atomic_store(all_cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                uint32_t was[kSyncGroups];
+#pragma unroll
+                for (int i = 0; i < kSyncGroups; i++)
+                    if (i < n_grp) was[i] = atomicExch(&flags[i * kSyncStride], 0x80000000u | am);
+                // the publisher is one more user of every flag: counted in once the flag is out
+#pragma unroll
+                for (int i = 0; i < kSyncGroups; i++)
+                    if (i < n_grp && atomicAdd(&users[i * kSyncStride], after_value(1u, was[i])) == (uint32_t)((G - i + kSyncGroups - 1) / kSyncGroups)) {
+                        __hip_atomic_store(&flags[i * kSyncStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(&users[i * kSyncStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
             }
         }
         uint32_t polls = 0, flag;
@@ -769,6 +788,7 @@ __global__ __launch_bounds__(kQuantThreads, 2) void k_quant_persist(const uint16
             polls++;
             __builtin_amdgcn_s_sleep(8);
         }
+        my_use = atomicAdd(&users[grp * kSyncStride], 1u);      // done with the flag, seen or not
         red[kQuantThreads / kWave] = flag;
     }
     __syncthreads();
@@ -825,6 +845,13 @@ __global__ __launch_bounds__(kQuantThreads, 2) void k_quant_persist(const uint16
         load_tile(ra, x, sh, r0, c0);
         quant_tile_body<ROW, COL, CEIL, false>(ra, sh, r0, c0, g, q_row, e_row, q_col, e_col, lds);
         __syncthreads();
+    }
+    // the last of a flag's users (the group's members and the publisher) leaves flag and count at zero
+    if (threadIdx.x == 0 && my_use == members) {
+        const int grp = first % kSyncGroups;
+        uint32_t *flags = sync + 2 * kSyncGroups * kSyncStride, *users = sync + 3 * kSyncGroups * kSyncStride;
+        __hip_atomic_store(&flags[grp * kSyncStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&users[grp * kSyncStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -919,7 +946,7 @@ static int quant_check_args(const void *x_bf16, int64_t rows, int64_t cols, int6
 {
     using namespace moss;
     const bool want_row = flags & MOSS_Q_ROW, want_col = flags & MOSS_Q_COL;
-    if (flags & ~(MOSS_Q_ROW | MOSS_Q_COL | MOSS_EXP_CEIL)) return MOSS_ERR_UNSUPPORTED;
+    if (flags & ~(MOSS_Q_ROW | MOSS_Q_COL | MOSS_EXP_CEIL | MOSS_WS_KEPT)) return MOSS_ERR_UNSUPPORTED;
     if (!want_row && !want_col) return MOSS_ERR_UNSUPPORTED;
     if (!x_bf16 || !s_global) return MOSS_ERR_NULL;
     if (want_row && (!q_row || !e_row)) return MOSS_ERR_NULL;
@@ -939,7 +966,7 @@ static int quant_check_args(const void *x_bf16, int64_t rows, int64_t cols, int6
 // `workspace`, wherever that memory comes from.  Arguments already checked.
 static int quant_with_workspace(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,
                                 uint8_t *q_row, uint8_t *e_row, uint8_t *q_col, uint8_t *e_col,
-                                float *s_global, void *workspace, void *stream)
+                                float *s_global, void *workspace, bool words_are_zero, void *stream)
 {
     using namespace moss;
     const bool want_row = flags & MOSS_Q_ROW, want_col = flags & MOSS_Q_COL, ceil_mode = flags & MOSS_EXP_CEIL;
@@ -962,8 +989,10 @@ static int quant_with_workspace(const void *x_bf16, int64_t rows, int64_t cols, 
         const int64_t grid = (int64_t)per_cu * moss_internal_cu_count();
         if (per_cu > 0 && n_tiles >= grid && n_tiles <= grid * kKeep) {
             uint32_t *sync = partial + kMaxPartials;
-            hipLaunchKernelGGL(k_quant_sync_reset, dim3(1), dim3(kQuantThreads), 0, st, sync);
-            MOSS_LAUNCH_CHECK();
+            if (!words_are_zero) {       // (the kernel leaves them at zero itself)
+                hipLaunchKernelGGL(k_quant_sync_reset, dim3(1), dim3(kQuantThreads), 0, st, sync);
+                MOSS_LAUNCH_CHECK();
+            }
             hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(kQuantThreads), 0, st, x, rows, cols, ld, (int)tiles_x,
                                (int)n_tiles, sync, g_poll_limit.load(), q_row, e_row, q_col, e_col, s_global);
             MOSS_LAUNCH_CHECK();
@@ -989,7 +1018,8 @@ extern "C" int moss_quant_act_2level(const void *x_bf16, int64_t rows, int64_t c
     if (rc != MOSS_OK) return rc;
     if (!moss_aligned16(workspace)) return MOSS_ERR_ALIGN;
     if (!workspace || workspace_bytes < moss_quant_workspace_bytes(rows, cols, flags)) return MOSS_ERR_WORKSPACE;
-    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, workspace, stream);
+    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, workspace,
+                                (flags & MOSS_WS_KEPT) != 0, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1038,9 +1068,10 @@ extern "C" int moss_quant_act_2level_noalloc(const void *x_bf16, int64_t rows, i
     void *ws = nullptr;
     rc = scratch_of_current_device(&ws);
     if (rc != MOSS_OK) return rc;
-    // nothing in the array has to start at a known value: the partial maxima are written before they are
-    // read, and the one-launch path clears its meeting words with a kernel of its own on the same stream
-    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, ws, stream);
+    // The partial maxima are written before they are read.  The meeting words of the one-launch path have
+    // to start at zero: the array is zero when the library is loaded, only this entry point writes to it,
+    // and the one-launch kernel clears every word it used before it ends, so no clearing launch is needed.
+    return quant_with_workspace(x_bf16, rows, cols, ld, flags, q_row, e_row, q_col, e_col, s_global, ws, true, stream);
 }
 
 extern "C" int moss_quant_act_2level_given_max(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld, unsigned flags,

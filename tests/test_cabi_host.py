@@ -58,6 +58,7 @@ def test_quant_argument_validation(L):
     assert q(FAKE, 32, 32, 32, 1, wsb=16) == 4            # workspace too small
     assert q(FAKE, 32, 32, 32, 0) == 5                    # no output requested
     assert q(FAKE, 32, 32, 32, 64) == 5                   # unknown flag
+    assert q(FAKE, 32, 48, 48, 1 | 8) == 2                # MOSS_WS_KEPT is a known flag: the shape error comes first
 
 
 def test_noalloc_argument_validation(L):
@@ -78,6 +79,7 @@ def test_producer_argument_validation(L):
     assert q(FAKE, 48, 32, 32, 2) == 2
     assert q(FAKE, 32, 32, 36, 1) == 3
     assert q(FAKE, 32, 32, 32, 1, mx=FAKE + 2) == 3       # misaligned maximum word
+    assert q(FAKE, 32, 32, 32, 1 | 8) == 5                # no workspace here, so no promise about one
     assert q(FAKE, 32, 32, 32, 0) == 5
     f = lambda g=FAKE, u=FAKE, rows=4, cols=8, ld=8, h=FAKE, m=FAKE: L.moss_swiglu_bf16(g, u, rows, cols, ld, h, m, None)
     assert f(g=None) == 1 and f(m=None) == 1

@@ -143,6 +143,31 @@ def test_one_launch_path_reuses_a_dirty_workspace(oracle):
         assert np.array_equal(u8(got["q_row"]), qr) and np.array_equal(u8(got["e_row"]), er)
 
 
+def test_kept_workspace_needs_no_clearing_launch(oracle):
+    """MOSS_WS_KEPT: a zero-filled workspace that only these calls write to.  The one-launch kernel leaves its
+    meeting words at zero, on the meeting path and on the timed-out path, so calls in a row (different shapes, the
+    last ones with polling switched off) give the oracle's outputs and the words read zero after every call."""
+    dev = torch.device("cuda:0")
+    ws = torch.zeros(moss.load().moss_quant_workspace_bytes(8192, 4096, 3), dtype=torch.uint8, device=dev)
+    calls = [((4096, 4096), 32768), ((2048, 4096), 32768), ((4000, 4128), 32768), ((8192, 4096), 32768),
+             ((4128, 2080), 0), ((2048, 4096), 0), ((4096, 4096), 32768)]
+    try:
+        for i, ((rows, cols), polls) in enumerate(calls):
+            print(f"[kept workspace] call {i}: {rows}x{cols} polls={polls}", flush=True)
+            xb = mi.heavy_tailed_activation(rows, cols, seed=70 + i)
+            moss.quant_set_poll_limit(polls)
+            got = moss.quant_act_2level(bf16_to_gpu(xb), ROW | COL | moss.MOSS_WS_KEPT, workspace=ws)
+            torch.cuda.synchronize()
+            assert int(ws[8192:].to(torch.int32).sum()) == 0, (i, "meeting words not back at zero")
+            qr, er, s = oracle.quant_act_2level(xb, 0, 0)
+            qc, ec, _ = oracle.quant_act_2level(xb, 1, 0)
+            assert scalar(got["s"]) == s, i
+            assert np.array_equal(u8(got["q_row"]), qr) and np.array_equal(u8(got["e_row"]), er), i
+            assert np.array_equal(u8(got["q_col"]), qc) and np.array_equal(u8(got["e_col"]), ec), i
+    finally:
+        moss.quant_set_poll_limit(32768)
+
+
 def test_row_stride_larger_than_cols(oracle):
     xb_full = mi.heavy_tailed_activation(96, 256, seed=31)
     x_full = bf16_to_gpu(xb_full)
