@@ -626,9 +626,34 @@ __device__ __forceinline__ bool quant_tile_body(const uint4 (&raw)[8], const Til
     return redo;
 }
 
+// Workgroup -> tile.  A tile leaves 4 exponent bytes per row and per column, pieces of memory lines that its
+// neighbours complete.  Workgroups are handed to the 8 XCDs in turn (workgroup id modulo 8) and each XCD has an
+// L2 of its own, so the tiles are dealt out in squares of kTileSquare x kTileSquare, a square to an XCD: the
+// pieces of a line then meet in one L2 and leave it as whole 32-byte sectors instead of one write-back each.
+constexpr int kXcds = 8;
+constexpr int kTileSquare = 8;
+
+__host__ __device__ inline int64_t tile_grid_size(int64_t tiles_x, int64_t tiles_y)
+{
+    const int64_t squares = ((tiles_x + kTileSquare - 1) / kTileSquare) * ((tiles_y + kTileSquare - 1) / kTileSquare);
+    return (squares + kXcds - 1) / kXcds * kXcds * (kTileSquare * kTileSquare);
+}
+
+// false: this workgroup's place in the grid lies outside the tensor (squares over the edge, padding of the grid)
+__device__ __forceinline__ bool tile_of_workgroup(uint32_t id, int tiles_x, int tiles_y, int &tx, int &ty)
+{
+    const uint32_t xcd = id % kXcds, k = id / kXcds;
+    const uint32_t square = k / (kTileSquare * kTileSquare) * kXcds + xcd, j = k % (kTileSquare * kTileSquare);
+    const uint32_t squares_x = (uint32_t)(tiles_x + kTileSquare - 1) / kTileSquare;
+    ty = (int)(square / squares_x * kTileSquare + j / kTileSquare);
+    tx = (int)(square % squares_x * kTileSquare + j % kTileSquare);
+    return tx < tiles_x && ty < tiles_y;
+}
+
 template <bool ROW, bool CEIL>
 __global__ __launch_bounds__(kQuantThreads, 4) void k_quant_tile(const uint16_t *__restrict__ x, int64_t rows, int64_t cols,
-                                                                 int64_t ld, const uint32_t *__restrict__ partial,
+                                                                 int64_t ld, int tiles_x, int tiles_y,
+                                                                 const uint32_t *__restrict__ partial,
                                                                  int n_partial, uint8_t *__restrict__ q_row,
                                                                  uint8_t *__restrict__ e_row, uint8_t *__restrict__ q_col,
                                                                  uint8_t *__restrict__ e_col, float *__restrict__ s_global)
@@ -636,13 +661,15 @@ __global__ __launch_bounds__(kQuantThreads, 4) void k_quant_tile(const uint16_t 
     __shared__ uint32_t red[kQuantThreads / kWave];
     __shared__ TileLds lds;
 
+    int tx, ty;
+    if (!tile_of_workgroup(blockIdx.x, tiles_x, tiles_y, tx, ty)) return;     // (the whole workgroup, before any barrier)
     converter_saturates();
     if (threadIdx.x == 0) lds.redo = 0;
     const GlobalScale g = fold_global_scale<CEIL>(partial, n_partial, red);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *s_global = g.s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *s_global = g.s;                 // (workgroup 0 has tile (0, 0))
 
     const TileShape sh = {rows, cols, ld};
-    const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
+    const int64_t r0 = (int64_t)ty * kTile, c0 = (int64_t)tx * kTile;
     uint4 raw[8];
     load_tile(raw, x, sh, r0, c0);
     bool general = true;
@@ -925,11 +952,11 @@ static int launch_codes(const uint16_t *x, int64_t rows, int64_t cols, int64_t l
     }
     if (want_col) {
         const int64_t gx = (cols + kTile - 1) / kTile, gy = (rows + kTile - 1) / kTile;
-        if (gy > 65535 || gx > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
-        const dim3 grid((unsigned)gx, (unsigned)gy), block(kQuantThreads);
+        if (gx > (1 << 24) || gy > (1 << 24) || tile_grid_size(gx, gy) > 0x7FFFFFFF) return MOSS_ERR_SHAPE;
+        const dim3 grid((unsigned)tile_grid_size(gx, gy)), block(kQuantThreads);
 #define MOSS_LAUNCH_TILE(R, C)                                                                                          \
-    hipLaunchKernelGGL((k_quant_tile<R, C>), grid, block, 0, st, x, rows, cols, ld, partial, n_partial, q_row, e_row, q_col, \
-                       e_col, s_global)
+    hipLaunchKernelGGL((k_quant_tile<R, C>), grid, block, 0, st, x, rows, cols, ld, (int)gx, (int)gy, partial, n_partial,  \
+                       q_row, e_row, q_col, e_col, s_global)
         if (want_row) { if (ceil_mode) MOSS_LAUNCH_TILE(true, true); else MOSS_LAUNCH_TILE(true, false); }
         else          { if (ceil_mode) MOSS_LAUNCH_TILE(false, true); else MOSS_LAUNCH_TILE(false, false); }
 #undef MOSS_LAUNCH_TILE
