@@ -34,9 +34,10 @@ TOKENS = 8192
 QUANT_BYTES_PER_ELEM_BOTH = 4.0625   # algorithmic: read 2 B, write 2 x (1 + 1/32) B
 QUANT_ONE_LAUNCH_MAX_ELEMS = 8192 * 4096   # up to here X is read once; larger tensors are read twice (6.0625 B/elem moved)
 WEIGHT_BYTES_PER_ELEM = 30.0         # W, m, v read+write (24) + FP32 grad (4) + codes (1) + transposed codes (1)
-# Mean bytes per launch crossing the L2 boundary (FETCH_SIZE and WRITE_SIZE from two rocprofv3 --pmc runs of this
-# script, each scaled by what the same counter reads for a plain copy; profiles/bench_config3_hbm_traffic.md).
-TRAFFIC_BYTES_PER_LAUNCH = {"gemm": 6.98e8, "quant": None, "weight": None}
+# Mean bytes per library call (all kernels of the call together; the GEMM is one launch) crossing the L2 boundary:
+# FETCH_SIZE and WRITE_SIZE from two rocprofv3 --pmc runs of this script, each scaled by what the same counter
+# reads for a plain copy (profiles/bench_config3_hbm_traffic.md).
+TRAFFIC_BYTES_PER_LAUNCH = {"gemm": 7.00e8, "quant": 3.11e8, "weight": 1.215e9}
 
 
 def log(*a):
