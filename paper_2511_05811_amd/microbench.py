@@ -20,6 +20,7 @@ are computed by tests/test_gpu_fidelity.py through the CPU oracle, which this pa
 """
 import argparse
 import json
+import os
 import sys
 
 
@@ -285,26 +286,38 @@ def quant(moss, torch, small=False):
 
 
 class _ClockPoller:
-    """Samples the shader clock with `rocm-smi --showclocks` (a child process that only reads sysfs)
-    while the GPU works."""
+    """Samples the shader clock (the starred line of the driver's pp_dpm_sclk file) and the board power
+    (hwmon power1_input) every two milliseconds while the GPU works."""
 
     def __init__(self):
+        import glob
         import threading
-        self.samples, self._stop = [], threading.Event()
+        f = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        h = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*"))
+        self._sclk_file = f[0] if f else None
+        self._hwmon = h[0] if h else None
+        self.sclk, self.power, self._stop = [], [], threading.Event()
         self._t = threading.Thread(target=self._run, daemon=True)
+
+    def power_cap_w(self):
+        try:
+            return int(open(os.path.join(self._hwmon, "power1_cap")).read()) / 1e6
+        except Exception:
+            return None
 
     def _run(self):
         import re
-        import subprocess
         while not self._stop.is_set():
             try:
-                out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
-                m = re.search(r"sclk clock level[^(]*\((\d+)Mhz\)", out)
-                if m:
-                    self.samples.append(int(m.group(1)))
+                if self._sclk_file:
+                    m = re.search(r"(\d+)Mhz \*", open(self._sclk_file).read())
+                    if m:
+                        self.sclk.append(int(m.group(1)))
+                if self._hwmon:
+                    self.power.append(int(open(os.path.join(self._hwmon, "power1_input")).read()) / 1e6)
             except Exception:
                 return
-            self._stop.wait(0.2)
+            self._stop.wait(0.002)
 
     def __enter__(self):
         self._t.start()
@@ -313,6 +326,11 @@ class _ClockPoller:
     def __exit__(self, *a):
         self._stop.set()
         self._t.join(timeout=15)
+
+    @staticmethod
+    def quantiles(v):
+        v = sorted(v)
+        return [v[int(q * (len(v) - 1))] for q in (0.1, 0.5, 0.9)] if v else None
 
 
 def limits(moss, torch, small=False):
@@ -336,7 +354,7 @@ def limits(moss, torch, small=False):
              ("uniformly random codes", torch.randint(0, 120, (M, K), dtype=torch.uint8, device=dev, generator=gen),
               torch.randint(0, 120, (N, K), dtype=torch.uint8, device=dev, generator=gen), ae),
              ("quantized Gaussians", qx["q_row"], qw["q_row"], qx["e_row"])]
-    rows = []
+    rows, cap = [], None
     for name, a, b, e in cases:
         for _ in range(3):
             moss.gemm_fp8_mx(a, e, one, b, None, one, out=out)
@@ -350,16 +368,17 @@ def limits(moss, torch, small=False):
                 torch.cuda.synchronize()
                 n += 20
             dt = time.time() - t0
-        clk = sorted(poll.samples[1:-1] or poll.samples)
         rows.append({"operands": name, "us_per_gemm": round(dt / n * 1e6, 1), "tflops": round(2.0 * M * N * K * n / dt / 1e12, 1),
-                     "sclk_mhz_median": clk[len(clk) // 2] if clk else None, "sclk_samples": len(clk)})
+                     "sclk_mhz_p10_p50_p90": poll.quantiles(poll.sclk), "board_power_w_p10_p50_p90": poll.quantiles(poll.power),
+                     "samples": len(poll.sclk)})
+        cap = poll.power_cap_w()
     copies = []
     for mb in ([8] if small else [64, 1024]):
         src = torch.empty(mb << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         ms, _ = _time_ms(torch, lambda: dst.copy_(src), 10)
         copies.append({"mib": mb, "ms": round(ms, 4), "gbs_read_plus_write": round(2.0 * (mb << 20) / ms / 1e6, 1)})
-    return {"table": "limits", "gemm_shape": [M, N, K], "gemm_by_operand_content": rows, "device_copy": copies}
+    return {"table": "limits", "gemm_shape": [M, N, K], "board_power_cap_w": cap, "gemm_by_operand_content": rows, "device_copy": copies}
 
 
 def main(argv=None):
